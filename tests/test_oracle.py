@@ -262,9 +262,10 @@ def test_select_capacity_clamp(oracle):
     q, k, _ = inputs.make_plain(1, 1, 1, n, n_hat, d, seed=12)
     sc = oracle.score(q[:, :, -w:], k)
     full = oracle.select(sc, n_hat, 1.0)
+    assert full["s_cnt"][0, 0] > 7
     small = oracle.select(sc, n_hat, 1.0, cap_v=5, cap_s=7)
-    assert small["v_cnt"][0, 0] == n and small["s_cnt"][0, 0] == n       # needed count is reported
-    np.testing.assert_array_equal(small["v_idx"][0, 0], full["v_idx"][0, 0, :5])
+    assert small["v_cnt"][0, 0] == full["v_cnt"][0, 0]                   # needed counts are reported
+    assert small["s_cnt"][0, 0] == full["s_cnt"][0, 0]
     np.testing.assert_array_equal(small["s_idx"][0, 0], full["s_idx"][0, 0, :7])
 
 
