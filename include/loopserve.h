@@ -1,0 +1,160 @@
+/*
+ * loopserve.h -- C ABI of libloopserve: the per-layer hot path of LoopServe's online-sparsified
+ * prefill attention and its decode-time KV retention scorer (arxiv 2507.13681), for AMD MI355X
+ * (gfx950).  Plain C, no exceptions cross this boundary.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers on the context's GPU, 16-byte aligned, row-major and
+ *     contiguous in the stated shape.  Only ls_shape and scalars are host data.
+ *   - The caller owns every tensor.  The library owns only the context and its workspace, which is
+ *     allocated once in ls_create; no entry point below allocates or frees device memory.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream) and contain
+ *     no host synchronisation; outputs are valid once the stream reaches the end of the call.
+ *     Counts (v_cnt, s_cnt, keep_cnt) stay on the device, so score -> select -> prefill chain without
+ *     a host round trip.  Calls that share a context must be issued on one stream at a time (they
+ *     share the workspace).
+ *   - Return value: LS_OK or a negative ls_status; ls_last_error(ctx) then describes the failure.
+ *     Argument errors are detected on the host before anything is launched.
+ *   - dtype is the storage type of q / k / v / out (bf16 or fp32); tile products accumulate in fp32
+ *     and every line weight, count and index output is fp32 / int32 regardless of dtype.
+ *   - Query head h reads KV head h / (Hq / Hkv)  (grouped-query attention).
+ *   - Positions: the context has n keys at positions 0..n-1; the newest turn is the last n_hat of
+ *     them; new-turn row a sits at absolute position n - n_hat + a and sees keys <= that position.
+ */
+#ifndef LOOPSERVE_H
+#define LOOPSERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ls_ctx ls_ctx;
+
+typedef enum {
+    LS_OK = 0,
+    LS_EINVAL = -1,      /* null or misaligned pointer, bad enum */
+    LS_ESHAPE = -2,      /* unsupported or inconsistent shape */
+    LS_EALPHA = -3,      /* alpha outside [0, 1] */
+    LS_EWORKSPACE = -4,  /* context workspace too small for this call */
+    LS_EHIP = -5         /* a HIP runtime call failed */
+} ls_status;
+
+typedef enum { LS_BF16 = 0, LS_F32 = 1 } ls_dtype;
+
+/* Limits: d in {64, 128}; w <= 256; n <= LS_MAX_N for ls_select / ls_sparse_prefill. */
+#define LS_MAX_N 262144
+#define LS_MAX_W 256
+
+typedef struct {
+    int32_t B;       /* batch */
+    int32_t Hq;      /* query heads */
+    int32_t Hkv;     /* KV heads, divides Hq */
+    int32_t d;       /* head dimension */
+    int64_t n;       /* keys in the context (cache length for ls_kv_compress) */
+    int64_t n_hat;   /* rows of the newest turn, 1 <= n_hat <= n (ignored by ls_kv_compress) */
+    int32_t w;       /* scoring rows: window size (n_obs for ls_kv_compress) */
+    int32_t dtype;   /* ls_dtype */
+    float scale;     /* logit scale; <= 0 means 1/sqrt(d) */
+} ls_shape;
+
+/* Bytes of workspace that every call on `shape` (and ls_kv_compress with `budget`) fits in.
+ * Host-only, no GPU needed.  Returns 0 for an invalid shape. */
+size_t ls_workspace_bytes(const ls_shape* shape, int32_t budget);
+
+/* Creates a context on GPU `device` with a workspace of `workspace_bytes` (device memory, allocated
+ * here, freed by ls_destroy).  The context can serve any shape whose ls_workspace_bytes fits. */
+int ls_create(ls_ctx** out, int device, size_t workspace_bytes);
+void ls_destroy(ls_ctx* ctx);
+/* Message of the last failing call on this context (never NULL; not thread-safe). */
+const char* ls_last_error(const ls_ctx* ctx);
+
+/*
+ * ls_score -- Alg. 2, steps "A = Softmax(Q~ K^T / sqrt(d_k))", SlashSum, VerticalSum (Appendix,
+ * Algorithm "Adaptive Prefilling Sparsification"), with the line definitions of Sec. 3.1 (Obs. 1):
+ * a vertical line is a key column, a slash line is a diagonal.
+ *
+ *   q_win  [B,Hq,w,d]   queries of the scoring rows
+ *   q_pos  [w] int64    their absolute positions (each clipped to [0, n-1]), device memory; NULL = the last w
+ *                       positions n-w .. n-1 (the newest query window)
+ *   k      [B,Hkv,n,d]
+ * Outputs (fp32):
+ *   vert   [B,Hq,n]  vert[b]  = sum_t A[t][b]              (column b)
+ *   slash  [B,Hq,n]  slash[o] = sum_t A[t][p_t - o]        (diagonal o = query pos - key pos)
+ *   vmax, smax [B,Hq,n]  the largest single entry of each line (the w^max of Alg. 2)
+ *   total  [B,Hq]    sum of all entries of A (about w)
+ * The softmax is causal (row t sees keys <= p_t).  With q_pos == NULL and w <= 128 all sums are
+ * formed in a fixed order (bit-reproducible); otherwise the diagonal sums use fp32 atomics.
+ */
+int ls_score(ls_ctx* ctx, const ls_shape* shape, const void* q_win, const int64_t* q_pos, const void* k,
+             float* vert, float* slash, float* vmax, float* smax, float* total, void* hip_stream);
+
+/*
+ * ls_select -- Alg. 2 from Desc_Sort to the end of the while-loop: both line lists are sorted by
+ * weight (descending; ties: smaller index first) and the greedy loop takes list heads until the
+ * accounted weight reaches alpha * total.  Gain of a slash is w_s - ol_v, of a vertical w_v - ol_s,
+ * where ol_* sums w^max of the lines taken from the other list; cost is max(1, length - #taken from
+ * the other list) with length min(n_hat, n - index); the slash is taken when gain_s * cost_v >=
+ * gain_v * cost_s; gains are not clamped; an empty list defers to the other.  All in binary32.
+ *
+ *   vert, slash, vmax, smax [B,Hq,n], total [B,Hq]   as produced by ls_score
+ * Outputs:
+ *   v_idx [B,Hq,cap_v] int32  selected columns, ascending;   v_cnt [B,Hq] int32
+ *   s_idx [B,Hq,cap_s] int32  selected diagonals, ascending; s_cnt [B,Hq] int32
+ *   accounted [B,Hq] fp32 or NULL: the loop's final sum.
+ * A count larger than its capacity means the list was truncated to the smallest `cap` indices.
+ * With accounted == NULL the loop stops as soon as the result is decided (when no remaining line
+ * has a positive gain every line ends up selected); with accounted != NULL it runs to the end.
+ * shape->w and dtype are ignored.  n <= LS_MAX_N.
+ */
+int ls_select(ls_ctx* ctx, const ls_shape* shape, float alpha,
+              const float* vert, const float* slash, const float* vmax, const float* smax, const float* total,
+              int32_t* v_idx, int32_t* v_cnt, int32_t cap_v,
+              int32_t* s_idx, int32_t* s_cnt, int32_t cap_s,
+              float* accounted, void* hip_stream);
+
+/*
+ * ls_sparse_prefill -- masked attention Softmax(QK^T/sqrt(d_k) - c(1-M)) V of Sec. 2.2 for the
+ * rows of the newest turn (Sec. 5, Step 1), with M[a][b] = 1 iff b <= p_a and (b in v_idx or
+ * p_a - b in s_idx), masked entries weighing exactly zero, each allowed cell counted once.
+ *
+ *   q [B,Hq,n_hat,d]; k, v [B,Hkv,n,d]; index lists as written by ls_select (device memory;
+ *   min(cnt, cap) entries are read).
+ * Outputs:
+ *   out [B,Hq,n_hat,d] in dtype; a row with no allowed cell is all zeros
+ *   lse [B,Hq,n_hat] fp32 or NULL: natural log of the softmax denominator (-inf for an empty row)
+ * n <= LS_MAX_N.  shape->w is ignored.
+ */
+int ls_sparse_prefill(ls_ctx* ctx, const ls_shape* shape, const void* q, const void* k, const void* v,
+                      const int32_t* v_idx, const int32_t* v_cnt, int32_t cap_v,
+                      const int32_t* s_idx, const int32_t* s_cnt, int32_t cap_s,
+                      void* out, float* lse, void* hip_stream);
+
+/*
+ * ls_kv_compress -- Alg. 3, the re-selection step (Sec. 5.2): for each KV head keep the `budget`
+ * cache entries that receive the most attention from the last n_obs = shape->w query rows, summed
+ * over the Hq/Hkv query heads of the group; ties go to the smaller index.
+ *
+ *   q_obs [B,Hq,n_obs,d]  queries at positions len-n_obs .. len-1 (len = shape->n)
+ *   k [B,Hkv,len,d]; v [B,Hkv,len,d] or NULL when v_out is NULL
+ * Outputs:
+ *   keep_idx [B,Hkv,budget] int32 ascending; keep_cnt [B,Hkv] = min(budget, len)
+ *   k_out, v_out [B,Hkv,budget,d] compacted copies of the kept rows, or NULL
+ */
+int ls_kv_compress(ls_ctx* ctx, const ls_shape* shape, int32_t budget,
+                   const void* q_obs, const void* k, const void* v,
+                   int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* hip_stream);
+
+/*
+ * Test hook: copies the retention score [B,Hkv,len] fp32 (column sums of the last n_obs rows, summed
+ * over each KV group, Sec. 5.2) that the most recent ls_kv_compress call on this context left in
+ * the workspace to `dst_device`.  `shape` must be the shape of that call.
+ */
+int ls_debug_copy_compress_score(ls_ctx* ctx, const ls_shape* shape, float* dst_device, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOOPSERVE_H */

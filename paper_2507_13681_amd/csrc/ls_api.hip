@@ -1,0 +1,269 @@
+// C-ABI entry points of libloopserve: argument checks, workspace carving, kernel dispatch.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/loopserve.h"
+#include "ls_internal.h"
+
+struct ls_ctx {
+    int device;
+    unsigned char* ws;
+    size_t ws_bytes;
+    char err[256];
+};
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+int fail(ls_ctx* c, int code, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Bump {
+    unsigned char* base; size_t cap, off;
+    template <typename T> T* take(size_t count) {
+        const size_t bytes = up(count * sizeof(T));
+        if (off + bytes > cap) { off = cap + 1; return nullptr; }
+        T* p = reinterpret_cast<T*>(base + off);
+        off += bytes;
+        return p;
+    }
+    bool ok() const { return off <= cap; }
+};
+
+// common shape checks; `what` selects which fields matter
+const char* check_shape(const ls_shape* s, bool need_nhat, bool need_w, bool cap_n) {
+    if (!s) return "shape is NULL";
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0) return "B, Hq, Hkv must be positive";
+    if (s->Hq % s->Hkv) return "Hq must be a multiple of Hkv";
+    if (s->d != 64 && s->d != 128) return "d must be 64 or 128";
+    if (s->dtype != LS_BF16 && s->dtype != LS_F32) return "dtype must be LS_BF16 or LS_F32";
+    if (s->n <= 0 || s->n > 2147483000LL) return "n out of range";
+    if (cap_n && s->n > LS_MAX_N) return "n exceeds LS_MAX_N";
+    if (need_nhat && (s->n_hat <= 0 || s->n_hat > s->n)) return "need 1 <= n_hat <= n";
+    if (need_w && (s->w <= 0 || s->w > LS_MAX_W || s->w > s->n)) return "need 1 <= w <= min(n, LS_MAX_W)";
+    if ((int64_t)s->B * s->Hq > 65535) return "B * Hq too large";
+    return nullptr;
+}
+
+inline int nkb_of(int64_t n) { return (int)((n + 127) / 128); }
+inline float scale_log2e(const ls_shape* s) {
+    const float sc = s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d);
+    return sc * 1.44269504088896340736f;
+}
+
+size_t ws_score(const ls_shape* s, bool lines) {
+    const size_t BH = (size_t)s->B * s->Hq;
+    size_t b = up(BH * s->w * nkb_of(s->n) * 2 * 4) + up(BH * s->w * 2 * 4);
+    if (lines) b += up(2 * BH * (size_t)s->n * 2 * 4);
+    return b;
+}
+size_t ws_select(const ls_shape* s) {
+    const size_t BH = (size_t)s->B * s->Hq;
+    return 6 * up(2 * BH * (size_t)s->n * 4);
+}
+inline int words_of(int64_t n) { return (int)((n + 31) / 32) + 8; }
+inline int tab_len_of(int64_t n) { return (int)(n / 64) + 4; }
+size_t ws_prefill(const ls_shape* s) {
+    const size_t BH = (size_t)s->B * s->Hq;
+    return 2 * up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n));
+}
+size_t ws_compress(const ls_shape* s) {
+    return ws_score(s, false) + up((size_t)s->B * s->Hkv * (size_t)s->n * 4);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ls_workspace_bytes(const ls_shape* s, int32_t budget) {
+    (void)budget;
+    if (check_shape(s, false, false, false)) return 0;
+    ls_shape t = *s;
+    if (t.w <= 0) t.w = 1;
+    size_t m = ws_score(&t, true);
+    if (ws_select(&t) > m) m = ws_select(&t);
+    if (ws_prefill(&t) > m) m = ws_prefill(&t);
+    if (ws_compress(&t) > m) m = ws_compress(&t);
+    return m + ALIGN;
+}
+
+int ls_create(ls_ctx** out, int device, size_t workspace_bytes) {
+    if (!out) return LS_EINVAL;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return LS_EHIP;
+    if (hipSetDevice(device) != hipSuccess) return LS_EHIP;
+    ls_ctx* c = new (std::nothrow) ls_ctx();
+    if (!c) return LS_EINVAL;
+    c->device = device; c->ws = nullptr; c->ws_bytes = workspace_bytes; c->err[0] = 0;
+    if (workspace_bytes) {
+        void* p = nullptr;
+        if (hipMalloc(&p, workspace_bytes) != hipSuccess) { delete c; return LS_EWORKSPACE; }
+        c->ws = static_cast<unsigned char*>(p);
+    }
+    *out = c;
+    return LS_OK;
+}
+
+void ls_destroy(ls_ctx* c) {
+    if (!c) return;
+    if (c->ws) { (void)hipSetDevice(c->device); (void)hipFree(c->ws); }
+    delete c;
+}
+
+const char* ls_last_error(const ls_ctx* c) { return c ? c->err : "context is NULL"; }
+
+int ls_score(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_pos, const void* k,
+             float* vert, float* slash, float* vmax, float* smax, float* total, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, false, true, false)) return fail(c, LS_ESHAPE, "ls_score: %s", m);
+    if (!q_win || !k || !vert || !slash || !vmax || !smax || !total) return fail(c, LS_EINVAL, "ls_score: NULL tensor");
+    if (!aligned16(q_win) || !aligned16(k) || !aligned16(vert) || !aligned16(slash) || !aligned16(vmax) ||
+        !aligned16(smax) || (q_pos && (reinterpret_cast<uintptr_t>(q_pos) & 7u)))
+        return fail(c, LS_EINVAL, "ls_score: misaligned tensor");
+    if (ls::score_lines_smem(s->w) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_score: w too large for LDS");
+    ls::ScoreArgs a{};
+    a.q = q_win; a.k = k; a.q_pos = q_pos; a.n = s->n; a.w = s->w; a.G = s->Hq / s->Hkv; a.Hq = s->Hq;
+    a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
+    Bump bp{c->ws, c->ws_bytes, 0};
+    a.part = bp.take<float>((size_t)a.BH * a.w * a.nkb * 2);
+    a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
+    a.spart = bp.take<float>(2 * (size_t)a.BH * (size_t)a.n * 2);
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_score: workspace of %zu bytes is too small", c->ws_bytes);
+    a.vert = vert; a.slash = slash; a.vmax = vmax; a.smax = smax; a.total = total; a.gscore = nullptr;
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_score: hipSetDevice failed");
+    const int mode = (q_pos == nullptr && s->w <= 128) ? 0 : 1;
+    const hipError_t e = ls::run_score(a, s->dtype, s->d, mode, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_score: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
+int ls_select(ls_ctx* c, const ls_shape* s, float alpha,
+              const float* vert, const float* slash, const float* vmax, const float* smax, const float* total,
+              int32_t* v_idx, int32_t* v_cnt, int32_t cap_v, int32_t* s_idx, int32_t* s_cnt, int32_t cap_s,
+              float* accounted, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, true, false, true)) return fail(c, LS_ESHAPE, "ls_select: %s", m);
+    if (!(alpha >= 0.f && alpha <= 1.f)) return fail(c, LS_EALPHA, "ls_select: alpha %g outside [0, 1]", (double)alpha);
+    if (!vert || !slash || !vmax || !smax || !total || !v_idx || !v_cnt || !s_idx || !s_cnt)
+        return fail(c, LS_EINVAL, "ls_select: NULL tensor");
+    if (cap_v <= 0 || cap_s <= 0) return fail(c, LS_ESHAPE, "ls_select: capacities must be positive");
+    ls::SelectArgs a{};
+    a.n = s->n; a.n_hat = s->n_hat; a.BH = s->B * s->Hq; a.alpha = alpha;
+    a.vert = vert; a.slash = slash; a.vmax = vmax; a.smax = smax; a.total = total;
+    Bump bp{c->ws, c->ws_bytes, 0};
+    const size_t cnt = 2 * (size_t)a.BH * (size_t)a.n;
+    a.skey0 = bp.take<uint32_t>(cnt); a.skey1 = bp.take<uint32_t>(cnt);
+    a.sidx0 = bp.take<int32_t>(cnt); a.sidx1 = bp.take<int32_t>(cnt);
+    a.sorted_w = bp.take<float>(cnt); a.sorted_m = bp.take<float>(cnt);
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_select: workspace of %zu bytes is too small", c->ws_bytes);
+    a.v_idx = v_idx; a.v_cnt = v_cnt; a.s_idx = s_idx; a.s_cnt = s_cnt; a.cap_v = cap_v; a.cap_s = cap_s;
+    a.accounted = accounted;
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_select: hipSetDevice failed");
+    const hipError_t e = ls::run_select(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_select: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
+int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k, const void* v,
+                      const int32_t* v_idx, const int32_t* v_cnt, int32_t cap_v,
+                      const int32_t* s_idx, const int32_t* s_cnt, int32_t cap_s,
+                      void* out, float* lse, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, true, false, true)) return fail(c, LS_ESHAPE, "ls_sparse_prefill: %s", m);
+    if (!q || !k || !v || !out || !v_idx || !v_cnt || !s_idx || !s_cnt)
+        return fail(c, LS_EINVAL, "ls_sparse_prefill: NULL tensor");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+        return fail(c, LS_EINVAL, "ls_sparse_prefill: misaligned tensor");
+    if (cap_v <= 0 || cap_s <= 0) return fail(c, LS_ESHAPE, "ls_sparse_prefill: capacities must be positive");
+    const int BH = s->B * s->Hq;
+    const int words = words_of(s->n), tab_len = tab_len_of(s->n);
+    if (ls::prefill_smem_bytes(s->dtype, s->d, words, tab_len) > 160 * 1024)
+        return fail(c, LS_ESHAPE, "ls_sparse_prefill: n too large for the LDS bitmaps");
+    Bump bp{c->ws, c->ws_bytes, 0};
+    uint32_t* obits = bp.take<uint32_t>((size_t)BH * words);
+    uint32_t* vbits = bp.take<uint32_t>((size_t)BH * words);
+    uint8_t* tab = bp.take<uint8_t>((size_t)BH * tab_len);
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_sparse_prefill: workspace of %zu bytes is too small", c->ws_bytes);
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: hipSetDevice failed");
+    ls::PlanArgs p{};
+    p.n = s->n; p.words = words; p.tab_len = tab_len; p.v_idx = v_idx; p.v_cnt = v_cnt; p.s_idx = s_idx; p.s_cnt = s_cnt;
+    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.vbits = vbits; p.tab = tab;
+    hipError_t e = ls::launch_plan(p, BH, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(plan): %s", hipGetErrorString(e));
+    ls::PrefillArgs a{};
+    a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.n = s->n; a.n_hat = s->n_hat;
+    a.pos0 = (s->n - s->n_hat) / 128 * 128;
+    a.Hq = s->Hq; a.Hkv = s->Hkv; a.G = s->Hq / s->Hkv; a.BH = BH;
+    a.nqb = (int)((s->n - a.pos0 + 127) / 128);
+    a.words = words; a.tab_len = tab_len; a.scale_log2e = scale_log2e(s);
+    a.obits = obits; a.vbits = vbits; a.tab = tab; a.v_idx = v_idx; a.v_cnt = v_cnt; a.cap_v = cap_v;
+    e = ls::launch_prefill(a, s->dtype, s->d, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
+int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_obs, const void* k, const void* v,
+                   int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, false, true, false)) return fail(c, LS_ESHAPE, "ls_kv_compress: %s", m);
+    if (budget <= 0) return fail(c, LS_ESHAPE, "ls_kv_compress: budget must be positive");
+    if (!q_obs || !k || !keep_idx || !keep_cnt || (v_out && !v)) return fail(c, LS_EINVAL, "ls_kv_compress: NULL tensor");
+    if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+        return fail(c, LS_EINVAL, "ls_kv_compress: misaligned tensor");
+    ls::ScoreArgs a{};
+    a.q = q_obs; a.k = k; a.q_pos = nullptr; a.n = s->n; a.w = s->w; a.G = s->Hq / s->Hkv; a.Hq = s->Hq;
+    a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
+    const int BK = s->B * s->Hkv;
+    Bump bp{c->ws, c->ws_bytes, 0};
+    a.part = bp.take<float>((size_t)a.BH * a.w * a.nkb * 2);
+    a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
+    a.gscore = bp.take<float>((size_t)BK * (size_t)a.n);
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_kv_compress: workspace of %zu bytes is too small", c->ws_bytes);
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress: hipSetDevice failed");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = ls::run_score(a, s->dtype, s->d, 2, st);
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(score): %s", hipGetErrorString(e));
+    ls::TopbArgs t{};
+    t.score = a.gscore; t.len = s->n; t.budget = budget; t.keep_idx = keep_idx; t.keep_cnt = keep_cnt;
+    e = ls::run_topb(t, BK, st);
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(topb): %s", hipGetErrorString(e));
+    const int row_bytes = s->d * (s->dtype == LS_BF16 ? 2 : 4);
+    if (k_out) {
+        e = ls::run_gather_rows(k, k_out, keep_idx, keep_cnt, BK, s->n, budget, row_bytes, st);
+        if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(gather k): %s", hipGetErrorString(e));
+    }
+    if (v_out) {
+        e = ls::run_gather_rows(v, v_out, keep_idx, keep_cnt, BK, s->n, budget, row_bytes, st);
+        if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(gather v): %s", hipGetErrorString(e));
+    }
+    return LS_OK;
+}
+
+/* Debug / test hook: the group-summed retention score of the last ls_kv_compress call on this
+ * context lives at the start of the third workspace block; exposed so tests can compare scores. */
+int ls_debug_copy_compress_score(ls_ctx* c, const ls_shape* s, float* dst_device, void* stream) {
+    if (!c || !s || !dst_device) return LS_EINVAL;
+    const size_t BH = (size_t)s->B * s->Hq;
+    const size_t off = up(BH * s->w * nkb_of(s->n) * 2 * 4) + up(BH * s->w * 2 * 4);
+    const size_t bytes = (size_t)s->B * s->Hkv * (size_t)s->n * 4;
+    if (off + bytes > c->ws_bytes) return LS_EWORKSPACE;
+    if (hipMemcpyAsync(dst_device, c->ws + off, bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return LS_EHIP;
+    return LS_OK;
+}
+
+}  // extern "C"

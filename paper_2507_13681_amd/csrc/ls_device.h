@@ -1,0 +1,97 @@
+// Device-side building blocks shared by the LoopServe kernels (gfx950 only).
+//
+// The tile products use the 32x32 MFMA shapes of CDNA4.  One "fragment" is the
+// 8 contraction-index values a lane feeds into a 32x32x16 product: lane l holds
+// row (or column) l % 32 of the operand and the eight k values 8*(l/32) .. +7 of
+// the current 16-wide k chunk.  For bf16 that is one v_mfma_f32_32x32x16_bf16;
+// for fp32 the same fragment is consumed by eight v_mfma_f32_32x32x2_f32, the
+// i-th pairing element i of both lane halves (a permutation of k, applied to
+// both operands alike, so the product is unchanged).
+//
+// Accumulator layout of every 32x32 product D = A * B (A is M x K, B is K x N):
+//   lane l, register r (0..15) holds D[8*(r/4) + 4*(l/32) + r%4][l % 32].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ls {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+struct bf16_t { uint16_t bits; };   // storage type tag for bf16 tensors
+
+template <typename T> struct Frag;
+template <> struct Frag<bf16_t> { bf16x8 v; };
+template <> struct Frag<float>  { float v[8]; };
+
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> { static constexpr int bytes = 2; static constexpr int per16 = 8; };
+template <> struct Elem<float>  { static constexpr int bytes = 4; static constexpr int per16 = 4; };
+
+// acc += A(32 x 16 chunk) * B(16 chunk x 32)
+__device__ __forceinline__ void mma(f32x16& acc, const Frag<bf16_t>& a, const Frag<bf16_t>& b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc, 0, 0, 0);
+}
+__device__ __forceinline__ void mma(f32x16& acc, const Frag<float>& a, const Frag<float>& b) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i], b.v[i], acc, 0, 0, 0);
+}
+
+// Load the 8 consecutive elements starting at p (16-byte aligned) as a fragment.
+__device__ __forceinline__ void load_frag(Frag<bf16_t>& f, const void* p) {
+    f.v = *reinterpret_cast<const bf16x8*>(p);
+}
+__device__ __forceinline__ void load_frag(Frag<float>& f, const void* p) {
+    const f32x4 a = reinterpret_cast<const f32x4*>(p)[0], b = reinterpret_cast<const f32x4*>(p)[1];
+    f.v[0] = a.x; f.v[1] = a.y; f.v[2] = a.z; f.v[3] = a.w;
+    f.v[4] = b.x; f.v[5] = b.y; f.v[6] = b.z; f.v[7] = b.w;
+}
+__device__ __forceinline__ void zero_frag(Frag<bf16_t>& f) {
+    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+    f.v = __builtin_bit_cast(bf16x8, z);
+}
+__device__ __forceinline__ void zero_frag(Frag<float>& f) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f.v[i] = 0.f;
+}
+
+// float -> bf16 bits, round to nearest even (inputs here are finite and non-negative).
+__device__ __forceinline__ uint16_t f2bf(float x) {
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint16_t b) {
+    return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+// Pack 8 probabilities into a fragment (operand of the P*V product).
+__device__ __forceinline__ void pack_frag(Frag<bf16_t>& f, const float* p) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(p[2 * i]) | ((uint32_t)f2bf(p[2 * i + 1]) << 16);
+    struct U4 { uint32_t a, b, c, d; } u = {w[0], w[1], w[2], w[3]};
+    f.v = __builtin_bit_cast(bf16x8, u);
+}
+__device__ __forceinline__ void pack_frag(Frag<float>& f, const float* p) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f.v[i] = p[i];
+}
+
+__device__ __forceinline__ float to_float(bf16_t x) { return bf2f(x.bits); }
+__device__ __forceinline__ float to_float(float x) { return x; }
+
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Key row `key` (0..63 inside a tile) sits at this column of the transposed V tile,
+// so that the 8 keys one lane half needs for a P*V chunk are contiguous:
+// bits 2 and 3 of the key index are swapped.
+__device__ __forceinline__ int vt_col(int key) {
+    return (key & ~12) | ((key & 8) >> 1) | ((key & 4) << 1);
+}
+
+}  // namespace ls

@@ -1,0 +1,75 @@
+// Host-side argument blocks and launchers shared by the translation units of libloopserve.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ls {
+
+struct ScoreArgs {
+    const void* q;            // [B,Hq,w,d]
+    const void* k;            // [B,Hkv,n,d]
+    const int64_t* q_pos;     // [w] or null
+    int64_t n;
+    int w, G, Hq, Hkv, B, BH, nkb;
+    float scale_log2e;
+    float* part;              // [BH*w][nkb][2]   per key block max / sum
+    float* rowstat;           // [BH*w][2]        row max, 1 / row sum
+    float* spart;             // [2][BH][n][2]    diagonal partial sum / max by key-block parity
+    float *vert, *slash, *vmax, *smax, *total;
+    float* gscore;            // [B*Hkv][n]       group-summed column sums (retention score)
+};
+
+struct SelectArgs {
+    int64_t n, n_hat;
+    int BH;
+    float alpha;
+    const float *vert, *slash, *vmax, *smax, *total;
+    uint32_t *skey0, *skey1;  // [2][BH][n] radix ping-pong keys
+    int32_t *sidx0, *sidx1;   // [2][BH][n] radix ping-pong indices (result in sidx1)
+    float *sorted_w, *sorted_m;   // [2][BH][n]
+    int32_t *v_idx, *v_cnt, *s_idx, *s_cnt;
+    int cap_v, cap_s;
+    float* accounted;         // may be null
+};
+
+struct TopbArgs {
+    const float* score;       // [BK][len]
+    int64_t len;
+    int budget;
+    int32_t *keep_idx, *keep_cnt;
+};
+
+struct PlanArgs {
+    int64_t n;
+    int words, tab_len;
+    const int32_t *v_idx, *v_cnt, *s_idx, *s_cnt;
+    int cap_v, cap_s;
+    uint32_t *obits, *vbits;  // [BH][words]
+    uint8_t* tab;             // [BH][tab_len]
+};
+
+struct PrefillArgs {
+    const void *q, *k, *v;
+    void* out;
+    float* lse;
+    int64_t n, n_hat, pos0;
+    int Hq, Hkv, G, BH, nqb, words, tab_len;
+    float scale_log2e;
+    const uint32_t *obits, *vbits;
+    const uint8_t* tab;
+    const int32_t *v_idx, *v_cnt;
+    int cap_v;
+};
+
+hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st);
+size_t score_lines_smem(int w);
+hipError_t run_select(const SelectArgs& a, hipStream_t st);
+hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st);
+hipError_t run_gather_rows(const void* src, void* dst, const int32_t* keep_idx, const int32_t* keep_cnt,
+                           int BK, int64_t len, int budget, int row_bytes, hipStream_t st);
+hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st);
+hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st);
+size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len);
+
+}  // namespace ls

@@ -1,0 +1,311 @@
+// Window scoring: attention of the newest query window over the whole context, reduced to
+// per-column ("vertical") and per-diagonal ("slash") sums and maxima (Alg. 2: the softmax step,
+// SlashSum and VerticalSum; Sec. 3.1 defines the two kinds of line).  The same kernels, in
+// "column sums only, summed over the query heads of a KV head" mode, produce the retention score
+// of Alg. 3 (Sec. 5.2).
+//
+// The softmax normaliser of a row is only known after all keys were seen, and the line sums mix
+// rows with different normalisers, so the pass is split:
+//   stats_kernel   per (row, 128-key block): max and sum of exp of the scaled logits;
+//   merge_kernel   per row: global max m and 1/l;
+//   lines_kernel   recomputes the logits, forms A = exp2(x - m) / l, and reduces it
+//                  - over rows, in registers, to column sums / maxima (written once, in order);
+//                  - over diagonals through an LDS copy of the 128-key slab of A, one thread per
+//                    diagonal adding the rows in fixed order; a diagonal crosses at most two key
+//                    blocks, whose two partial results finish_kernel adds.
+// Everything is summed in a fixed order, so results are bit-reproducible from run to run.
+// With explicit scoring positions (q_pos given) the diagonals of a slab are not a contiguous
+// range; that path uses fp32 atomics on zero-initialised outputs instead.
+//
+// Tile products run on 32x32 MFMA with K fragments held in registers (each wave owns 32 keys of
+// the block and re-uses them for every query head of the KV group and every 32-row group).
+#include "ls_device.h"
+#include "ls_internal.h"
+
+namespace ls {
+
+constexpr int SB = 128;           // keys per workgroup
+constexpr int SCORE_THREADS = 256;
+
+template <typename T, int D>
+__device__ __forceinline__ void load_k_frags(Frag<T> (&kf)[D / 16], const T* Kg, int64_t key, int64_t n, int g) {
+    if (key < n) {
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) load_frag(kf[c], Kg + key * D + 16 * c + 8 * g);
+    } else {
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) zero_frag(kf[c]);
+    }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void load_q_frags(Frag<T> (&qf)[D / 16], const T* Qh, int row, int w, int g) {
+    if (row < w) {
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) load_frag(qf[c], Qh + (int64_t)row * D + 16 * c + 8 * g);
+    } else {
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) zero_frag(qf[c]);
+    }
+}
+
+// ---- pass 1: per (row, key block) max and sum of exp2 -----------------------------------------
+// grid (nkb, B*Hkv).  part[(bh*w + row)*nkb + kb] = {max, sum}.
+template <typename T, int D>
+__global__ __launch_bounds__(SCORE_THREADS) void stats_kernel(ScoreArgs a) {
+    __shared__ float red[4][32][2];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, r32 = lane & 31, g = lane >> 5;
+    const int kb = blockIdx.x, bk = blockIdx.y;
+    const int b = bk / a.Hkv, kvh = bk % a.Hkv;
+    const int64_t n = a.n;
+    const T* Kg = reinterpret_cast<const T*>(a.k) + (int64_t)bk * n * D;
+    const int64_t key0 = (int64_t)kb * SB + 32 * wv;
+    Frag<T> kf[D / 16];
+    load_k_frags<T, D>(kf, Kg, key0 + r32, n, g);
+    const int rgs = (a.w + 31) / 32;
+    for (int gq = 0; gq < a.G; ++gq) {
+        const int bh = b * a.Hq + kvh * a.G + gq;
+        const T* Qh = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.w * D;
+        for (int rg = 0; rg < rgs; ++rg) {
+            const int row = 32 * rg + r32;
+            Frag<T> qf[D / 16];
+            load_q_frags<T, D>(qf, Qh, row, a.w, g);
+            f32x16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+            for (int c = 0; c < D / 16; ++c) mma(s, kf[c], qf[c]);   // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
+            int64_t p = (row < a.w) ? (a.q_pos ? a.q_pos[row] : n - a.w + row) : -1;
+            if (p > n - 1) p = n - 1;                  // positions outside the context are clipped
+            if (p < -1) p = -1;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t key = key0 + 8 * (r >> 2) + 4 * g + (r & 3);
+                const float x = (key <= p) ? s[r] * a.scale_log2e : -INFINITY;
+                s[r] = x;
+                mx = fmaxf(mx, x);
+            }
+            mx = fmaxf(mx, xor32(mx));
+            const float ms = (mx == -INFINITY) ? 0.f : mx;
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += fast_exp2(s[r] - ms);
+            sum += xor32(sum);
+            __syncthreads();
+            if (g == 0) { red[wv][r32][0] = mx; red[wv][r32][1] = sum; }
+            __syncthreads();
+            if (wv == 0 && g == 0 && row < a.w) {
+                float M = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) M = fmaxf(M, red[i][r32][0]);
+                const float Ms = (M == -INFINITY) ? 0.f : M;
+                float L = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) L += red[i][r32][1] * fast_exp2(red[i][r32][0] - Ms);
+                float* dst = a.part + (((int64_t)bh * a.w + row) * a.nkb + kb) * 2;
+                dst[0] = M; dst[1] = L;
+            }
+        }
+    }
+}
+
+// ---- merge: one thread per row ----------------------------------------------------------------
+__global__ void merge_kernel(ScoreArgs a, int rows) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    const float* p = a.part + (int64_t)i * a.nkb * 2;
+    float M = -INFINITY;
+    for (int kb = 0; kb < a.nkb; ++kb) M = fmaxf(M, p[2 * kb]);
+    float L = 0.f;
+    for (int kb = 0; kb < a.nkb; ++kb) {
+        const float m = p[2 * kb];
+        if (m != -INFINITY) L += p[2 * kb + 1] * fast_exp2(m - M);
+    }
+    a.rowstat[2 * i] = M;
+    a.rowstat[2 * i + 1] = L > 0.f ? 1.0f / L : 0.f;
+}
+
+// ---- pass 2: line sums ------------------------------------------------------------------------
+// grid (nkb, B*Hkv), dynamic LDS: A slab [w_pad][SB + 1] floats + row stats [w_pad][2] + positions.
+// MODE 0: vert/vmax per head + diagonal partials (contiguous window, q_pos == NULL)
+// MODE 1: vert/vmax per head + diagonals through atomics (explicit q_pos)
+// MODE 2: column sums only, summed over the G heads of the KV head (retention score)
+template <typename T, int D, int MODE>
+__global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int wpad = ((a.w + 31) / 32) * 32;
+    float* slab = reinterpret_cast<float*>(smem);                  // [wpad][SB+1]
+    float* rst = slab + (size_t)wpad * (SB + 1);                   // [wpad][2]
+    int64_t* qp = reinterpret_cast<int64_t*>(rst + 2 * wpad);      // [wpad]
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, r32 = lane & 31, g = lane >> 5;
+    const int kb = blockIdx.x, bk = blockIdx.y;
+    const int b = bk / a.Hkv, kvh = bk % a.Hkv;
+    const int64_t n = a.n;
+    const T* Kg = reinterpret_cast<const T*>(a.k) + (int64_t)bk * n * D;
+    const int64_t key0 = (int64_t)kb * SB + 32 * wv;
+    const int64_t mykey = key0 + r32;
+    Frag<T> kf[D / 16];
+    load_k_frags<T, D>(kf, Kg, mykey, n, g);
+    for (int i = tid; i < wpad; i += SCORE_THREADS) {
+        int64_t p = (i < a.w) ? (a.q_pos ? a.q_pos[i] : n - a.w + i) : -1;
+        if (p > n - 1) p = n - 1;                          // positions outside the context are clipped
+        if (p < -1) p = -1;
+        qp[i] = p;
+    }
+    const int rgs = wpad / 32;
+    float gsum = 0.f;                                              // MODE 2 accumulator over heads
+    for (int gq = 0; gq < a.G; ++gq) {
+        const int bh = b * a.Hq + kvh * a.G + gq;
+        const T* Qh = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.w * D;
+        __syncthreads();                                           // slab / rst free again
+        for (int i = tid; i < wpad; i += SCORE_THREADS) {
+            const bool ok = i < a.w;
+            rst[2 * i] = ok ? a.rowstat[2 * ((int64_t)bh * a.w + i)] : 0.f;
+            rst[2 * i + 1] = ok ? a.rowstat[2 * ((int64_t)bh * a.w + i) + 1] : 0.f;
+        }
+        __syncthreads();
+        float vsum = 0.f, vmx = 0.f;
+        for (int rg = 0; rg < rgs; ++rg) {
+            Frag<T> qf[D / 16];
+            load_q_frags<T, D>(qf, Qh, 32 * rg + r32, a.w, g);
+            f32x16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+            for (int c = 0; c < D / 16; ++c) mma(s, qf[c], kf[c]);   // s[r] = <q_{8(r/4)+4g+r%4}, k_lane>
+            float ps = 0.f, pm = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 32 * rg + 8 * (r >> 2) + 4 * g + (r & 3);
+                const float m = rst[2 * row], il = rst[2 * row + 1];
+                const float p = (mykey <= qp[row]) ? fast_exp2(s[r] * a.scale_log2e - m) * il : 0.f;
+                ps += p;
+                pm = fmaxf(pm, p);
+                if (MODE == 0) slab[row * (SB + 1) + 32 * wv + r32] = p;
+                if (MODE == 1 && p > 0.f) {
+                    const int64_t o = qp[row] - mykey;
+                    atomicAdd(a.slash + (int64_t)bh * n + o, p);
+                    atomicMax(reinterpret_cast<unsigned int*>(a.smax + (int64_t)bh * n + o),
+                              __builtin_bit_cast(unsigned int, p));
+                }
+            }
+            ps += xor32(ps);
+            pm = fmaxf(pm, xor32(pm));
+            vsum += ps;
+            vmx = fmaxf(vmx, pm);
+        }
+        if (MODE == 2) gsum += vsum;
+        else if (g == 0 && mykey < n) {
+            a.vert[(int64_t)bh * n + mykey] = vsum;
+            a.vmax[(int64_t)bh * n + mykey] = vmx;
+        }
+        if (MODE == 0) {
+            __syncthreads();
+            // thread j owns diagonal o = omin + j of this slab; key_local = t + (SB-1) - j for row t
+            const int64_t omin = n - a.w - ((int64_t)kb * SB + SB - 1);
+            for (int j = tid; j < SB - 1 + a.w; j += SCORE_THREADS) {
+                const int64_t o = omin + j;
+                if (o < 0) continue;
+                float ssum = 0.f, smx = 0.f;
+                const int t0 = j - (SB - 1) > 0 ? j - (SB - 1) : 0;
+                const int t1 = j < a.w - 1 ? j : a.w - 1;
+                for (int t = t0; t <= t1; ++t) {
+                    const float p = slab[t * (SB + 1) + t + (SB - 1) - j];
+                    ssum += p;
+                    smx = fmaxf(smx, p);
+                }
+                float* dst = a.spart + (((int64_t)(kb & 1) * a.BH + bh) * n + o) * 2;
+                dst[0] = ssum; dst[1] = smx;
+            }
+        }
+    }
+    if (MODE == 2 && g == 0 && mykey < n) a.gscore[(int64_t)bk * n + mykey] = gsum;
+}
+
+// ---- finish: add the two diagonal partials, reduce the total ------------------------------------
+// grid (B*Hq).  Diagonal o is met by keys n-w-o .. n-1-o (clipped at 0), i.e. by key blocks
+// kA = max(0, n-w-o)/SB and kB = (n-1-o)/SB, which are equal or adjacent.
+__global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguous) {
+    __shared__ float red[1024];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const int64_t n = a.n;
+    if (contiguous) {
+        for (int64_t o = tid; o < n; o += blockDim.x) {
+            int64_t lo = n - a.w - o; if (lo < 0) lo = 0;
+            const int64_t kA = lo / SB, kB = (n - 1 - o) / SB;
+            const float* pa = a.spart + (((kA & 1) * a.BH + bh) * n + o) * 2;
+            float s = pa[0], m = pa[1];
+            if (kB != kA) {
+                const float* pb = a.spart + (((kB & 1) * a.BH + bh) * n + o) * 2;
+                s = s + pb[0];                         // lower key block first
+                m = fmaxf(m, pb[1]);
+            }
+            a.slash[(int64_t)bh * n + o] = s;
+            a.smax[(int64_t)bh * n + o] = m;
+        }
+    }
+    // total = sum of the column sums, fixed tree order
+    float acc = 0.f;
+    for (int64_t i = tid; i < n; i += blockDim.x) acc += a.vert[(int64_t)bh * n + i];
+    red[tid] = acc;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) a.total[bh] = red[0];
+}
+
+__global__ void fill_zero_kernel(float* p, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+template <typename T, int D>
+static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
+    const dim3 grid(a.nkb, a.B * a.Hkv);
+    hipLaunchKernelGGL((stats_kernel<T, D>), grid, dim3(SCORE_THREADS), 0, st, a);
+    const int rows = a.BH * a.w;
+    hipLaunchKernelGGL(merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, a, rows);
+    const int wpad = ((a.w + 31) / 32) * 32;
+    const size_t smem = (size_t)wpad * (SB + 1) * 4 + (size_t)wpad * 8 + (size_t)wpad * 8;
+    hipError_t e;
+    if (mode == 0) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((lines_kernel<T, D, 0>), grid, dim3(SCORE_THREADS), smem, st, a);
+    } else if (mode == 1) {
+        const int64_t cnt = (int64_t)a.BH * a.n;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.slash, cnt);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.smax, cnt);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((lines_kernel<T, D, 1>), grid, dim3(SCORE_THREADS), smem, st, a);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((lines_kernel<T, D, 2>), grid, dim3(SCORE_THREADS), smem, st, a);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(finish_kernel, dim3(a.BH), dim3(1024), 0, st, a, mode == 0 ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st) {
+    if (dtype == 0 && d == 128) return run_score_t<bf16_t, 128>(a, mode, st);
+    if (dtype == 0 && d == 64) return run_score_t<bf16_t, 64>(a, mode, st);
+    if (dtype == 1 && d == 128) return run_score_t<float, 128>(a, mode, st);
+    if (dtype == 1 && d == 64) return run_score_t<float, 64>(a, mode, st);
+    return hipErrorInvalidValue;
+}
+
+size_t score_lines_smem(int w) {
+    const int wpad = ((w + 31) / 32) * 32;
+    return (size_t)wpad * (SB + 1) * 4 + (size_t)wpad * 16;
+}
+
+}  // namespace ls
