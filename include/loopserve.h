@@ -148,6 +148,17 @@ int ls_kv_compress(ls_ctx* ctx, const ls_shape* shape, int32_t budget,
                    int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* hip_stream);
 
 /*
+ * Timing of the sparse attention kernel itself (the dominant kernel of ls_sparse_prefill), for
+ * roofline reports.  After ls_profile_enable(ctx, 1) every ls_sparse_prefill call brackets that
+ * one kernel launch with HIP events on the call's stream (this creates two events per call, so
+ * leave it off in allocation-free loops).  ls_profile_prefill_kernel_ms waits for the recorded
+ * events and returns the mean kernel duration in milliseconds and the number of launches seen since
+ * profiling was enabled.  ls_profile_enable(ctx, 0) stops recording and drops the events.
+ */
+int ls_profile_enable(ls_ctx* ctx, int on);
+int ls_profile_prefill_kernel_ms(ls_ctx* ctx, double* mean_ms, int32_t* launches);
+
+/*
  * Test hook: copies the retention score [B,Hkv,len] fp32 (column sums of the last n_obs rows, summed
  * over each KV group, Sec. 5.2) that the most recent ls_kv_compress call on this context left in
  * the workspace to `dst_device`.  `shape` must be the shape of that call.

@@ -286,6 +286,10 @@ int lso_attend(int B, int Hq, int Hkv, int d, int64_t n, int64_t n_hat, double s
             const int32_t *vi = v_idx + bh * cap_v, *si = s_idx + bh * cap_s;
             const int64_t nv = v_cnt[bh], ns = s_cnt[bh];
             if (nv > cap_v || ns > cap_s) { rc = -4; continue; }
+            int bad = 0;                                /* every index must name a line of the block */
+            for (int64_t i = 0; i < nv; ++i) if (vi[i] < 0 || vi[i] >= n) bad = 1;
+            for (int64_t i = 0; i < ns; ++i) if (si[i] < 0 || si[i] >= n) bad = 1;
+            if (bad) { rc = -5; continue; }
             if (bh != cur_head) {                       /* membership tables of this head */
                 memset(col, 0, n); memset(off, 0, n);
                 for (int64_t i = 0; i < nv; ++i) col[vi[i]] = 1;

@@ -61,6 +61,10 @@ def load_library():
     lib.ls_kv_compress.argtypes = [vp, sp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ls_debug_copy_compress_score.restype = C.c_int
     lib.ls_debug_copy_compress_score.argtypes = [vp, sp, vp, vp]
+    lib.ls_profile_enable.restype = C.c_int
+    lib.ls_profile_enable.argtypes = [vp, C.c_int]
+    lib.ls_profile_prefill_kernel_ms.restype = C.c_int
+    lib.ls_profile_prefill_kernel_ms.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -135,6 +139,14 @@ class Context:
     def ls_kv_compress(self, shape, budget, q_obs, k, v, keep_idx, keep_cnt, k_out=None, v_out=None):
         self._check(self.lib.ls_kv_compress(self.h, C.byref(shape), budget, _ptr(q_obs), _ptr(k), _ptr(v),
                                             _ptr(keep_idx), _ptr(keep_cnt), _ptr(k_out), _ptr(v_out), _stream()))
+
+    def profile_enable(self, on=True):
+        self._check(self.lib.ls_profile_enable(self.h, 1 if on else 0))
+
+    def profile_prefill_kernel_ms(self):
+        ms, cnt = C.c_double(), C.c_int32()
+        self._check(self.lib.ls_profile_prefill_kernel_ms(self.h, C.byref(ms), C.byref(cnt)))
+        return ms.value, cnt.value
 
     def debug_compress_score(self, shape, dst):
         self._check(self.lib.ls_debug_copy_compress_score(self.h, C.byref(shape), _ptr(dst), _stream()))

@@ -4,6 +4,10 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <new>
+#include <utility>
+#include <vector>
+
 #include "../../include/loopserve.h"
 #include "ls_internal.h"
 
@@ -12,6 +16,9 @@ struct ls_ctx {
     unsigned char* ws;
     size_t ws_bytes;
     char err[256];
+    // optional timing of the sparse attention kernel (ls_profile_*): event pairs on the call's stream
+    bool profile;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
 };
 
 namespace {
@@ -108,7 +115,7 @@ int ls_create(ls_ctx** out, int device, size_t workspace_bytes) {
     if (hipSetDevice(device) != hipSuccess) return LS_EHIP;
     ls_ctx* c = new (std::nothrow) ls_ctx();
     if (!c) return LS_EINVAL;
-    c->device = device; c->ws = nullptr; c->ws_bytes = workspace_bytes; c->err[0] = 0;
+    c->device = device; c->ws = nullptr; c->ws_bytes = workspace_bytes; c->err[0] = 0; c->profile = false;
     if (workspace_bytes) {
         void* p = nullptr;
         if (hipMalloc(&p, workspace_bytes) != hipSuccess) { delete c; return LS_EWORKSPACE; }
@@ -120,7 +127,9 @@ int ls_create(ls_ctx** out, int device, size_t workspace_bytes) {
 
 void ls_destroy(ls_ctx* c) {
     if (!c) return;
-    if (c->ws) { (void)hipSetDevice(c->device); (void)hipFree(c->ws); }
+    (void)hipSetDevice(c->device);
+    for (auto& e : c->events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+    if (c->ws) (void)hipFree(c->ws);
     delete c;
 }
 
@@ -211,7 +220,17 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     a.nqb = (int)((s->n - a.pos0 + 127) / 128);
     a.words = words; a.tab_len = tab_len; a.scale_log2e = scale_log2e(s);
     a.obits = obits; a.vbits = vbits; a.tab = tab; a.v_idx = v_idx; a.v_cnt = v_cnt; a.cap_v = cap_v;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->profile) {
+        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+            return fail(c, LS_EHIP, "ls_sparse_prefill: hipEventCreate failed");
+        (void)hipEventRecord(e0, static_cast<hipStream_t>(stream));
+    }
     e = ls::launch_prefill(a, s->dtype, s->d, static_cast<hipStream_t>(stream));
+    if (c->profile) {
+        (void)hipEventRecord(e1, static_cast<hipStream_t>(stream));
+        c->events.emplace_back(e0, e1);
+    }
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: %s", hipGetErrorString(e));
     return LS_OK;
 }
@@ -250,6 +269,30 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
         e = ls::run_gather_rows(v, v_out, keep_idx, keep_cnt, BK, s->n, budget, row_bytes, st);
         if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(gather v): %s", hipGetErrorString(e));
     }
+    return LS_OK;
+}
+
+int ls_profile_enable(ls_ctx* c, int on) {
+    if (!c) return LS_EINVAL;
+    (void)hipSetDevice(c->device);
+    for (auto& e : c->events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+    c->events.clear();
+    c->profile = on != 0;
+    return LS_OK;
+}
+
+int ls_profile_prefill_kernel_ms(ls_ctx* c, double* mean_ms, int32_t* launches) {
+    if (!c || !mean_ms || !launches) return LS_EINVAL;
+    double tot = 0.0;
+    int cnt = 0;
+    for (auto& e : c->events) {
+        if (hipEventSynchronize(e.second) != hipSuccess) return fail(c, LS_EHIP, "ls_profile: hipEventSynchronize failed");
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e.first, e.second) != hipSuccess) return fail(c, LS_EHIP, "ls_profile: hipEventElapsedTime failed");
+        tot += ms; ++cnt;
+    }
+    *mean_ms = cnt ? tot / cnt : 0.0;
+    *launches = cnt;
     return LS_OK;
 }
 

@@ -1,0 +1,38 @@
+"""Host-side bookkeeping for reports: how many attention cells a selection allows.
+
+Not part of the compute path.  The count is exact and follows from the index sets alone:
+column b is crossed by min(n_hat, n - b) new-turn rows, diagonal o by min(n_hat, n - o), and a
+column and a diagonal share the one cell (row position b + o, key b) when that row belongs to
+the newest turn, i.e. n - n_hat <= b + o <= n - 1.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def allowed_cells(n: int, n_hat: int, v_idx, s_idx) -> int:
+    """Cells of the n_hat x n causal block covered by the union of the given lines."""
+    v = np.unique(np.asarray(v_idx, dtype=np.int64))
+    s = np.unique(np.asarray(s_idx, dtype=np.int64))
+    cells = int(np.minimum(n_hat, n - v).sum() + np.minimum(n_hat, n - s).sum())
+    if len(v) and len(s):
+        lo = np.searchsorted(v, n - n_hat - s, side="left")
+        hi = np.searchsorted(v, n - 1 - s, side="right")
+        cells -= int((hi - lo).sum())
+    return cells
+
+
+def selection_cells(n: int, n_hat: int, sel: dict) -> np.ndarray:
+    """allowed_cells for every (batch, head) of a selection dict (numpy arrays)."""
+    B, Hq = sel["v_cnt"].shape
+    out = np.zeros((B, Hq), np.int64)
+    for b in range(B):
+        for h in range(Hq):
+            nv = min(int(sel["v_cnt"][b, h]), sel["v_idx"].shape[-1])
+            ns = min(int(sel["s_cnt"][b, h]), sel["s_idx"].shape[-1])
+            out[b, h] = allowed_cells(n, n_hat, sel["v_idx"][b, h, :nv], sel["s_idx"][b, h, :ns])
+    return out
+
+
+def causal_cells(n: int, n_hat: int) -> int:
+    return n_hat * (n - n_hat) + n_hat * (n_hat + 1) // 2

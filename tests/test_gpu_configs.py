@@ -1,0 +1,171 @@
+"""End-to-end parity on the five benchmark workloads, at their full sizes and in the launch
+configuration bench.py times: score -> select -> sparse prefill (-> KV retention for the decode
+workload) through the C ABI, against the CPU oracle.
+
+  * line weights: every entry compared (rel 1e-3, abs 1e-6 * w);
+  * selected sets: must equal the oracle's, except for lines whose weight lies within 1e-3
+    (relative) of that list's selection threshold;
+  * attention outputs: compared on sampled rows (all rows for the tiny workload) against the
+    oracle evaluated on the device's own index sets: max-abs <= 2e-2, mean-abs <= 5e-3 for bf16,
+    1e-4 for fp32.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_13681_amd import inputs, metrics
+
+pytestmark = pytest.mark.gpu
+
+from tests.gpu_util import Pipeline, host  # noqa: E402
+
+
+def check_scores(gpu, ref, w):
+    for name in ("vert", "slash", "vmax", "smax"):
+        np.testing.assert_allclose(gpu[name], ref[name], rtol=1e-3, atol=1e-6 * w, err_msg=name)
+    np.testing.assert_allclose(gpu["total"], ref["total"], rtol=1e-5)
+
+
+def check_selection(gpu, ref, sc_ref, tol=1e-3):
+    """Sets equal up to lines at the selection threshold.  Returns the number of tolerated lines."""
+    B, Hq = ref["v_cnt"].shape
+    tolerated = 0
+    for b in range(B):
+        for h in range(Hq):
+            for idx, cnt, wname in (("v_idx", "v_cnt", "vert"), ("s_idx", "s_cnt", "slash")):
+                g = gpu[idx][b, h, :int(gpu[cnt][b, h])]
+                r = ref[idx][b, h, :int(ref[cnt][b, h])]
+                if len(g) == len(r) and np.array_equal(g, r):
+                    continue
+                wts = sc_ref[wname][b, h]
+                diff = np.setxor1d(g, r)
+                # threshold of the list = weight of the lightest line the oracle selected
+                # (or of the heaviest line when it selected none)
+                thr = wts[r].min() if len(r) else wts.max()
+                bad = np.abs(wts[diff] - thr) > tol * max(thr, 1e-30)
+                assert not bad.any(), (f"b={b} h={h} {wname}: {bad.sum()} of {len(diff)} differing lines are not at the "
+                                       f"threshold {thr:.3e} (gpu {len(g)} lines, oracle {len(r)})")
+                tolerated += len(diff)
+    return tolerated
+
+
+def sample_rows(cfg, per_head, rng):
+    """Flat row ids: the first, last and block-boundary rows of each head plus random ones."""
+    rows = []
+    nh = cfg.n_hat
+    first_block = 128 - (cfg.n - nh) % 128            # rows up to the first 128-aligned position
+    fixed = [0, 1, nh - 1, nh - 2, min(first_block, nh - 1), min(first_block + 1, nh - 1), nh // 2]
+    for bh in range(cfg.B * cfg.Hq):
+        pick = set(x for x in fixed if 0 <= x < nh)
+        pick.update(int(x) for x in rng.integers(0, nh, size=per_head))
+        rows.extend(bh * nh + a for a in sorted(pick))
+    return np.array(rows, np.int64)
+
+
+def check_attention(oracle, cfg, q, k, v, sel_gpu, out_gpu, lse_gpu, rows, mode=1):
+    ref_out, ref_lse = oracle.attend(q, k, v, sel_gpu["v_idx"], sel_gpu["v_cnt"], sel_gpu["s_idx"], sel_gpu["s_cnt"],
+                                     rows=rows, mode=mode)
+    got = out_gpu.reshape(-1, cfg.d)[torch.from_numpy(rows).to(out_gpu.device)].float().cpu().numpy()
+    err = np.abs(got - ref_out)
+    if cfg.dtype == "bf16":
+        assert err.max() <= 2e-2, err.max()
+        assert err.mean() <= 5e-3, err.mean()
+    else:
+        assert err.max() <= 1e-4, err.max()
+    lse = lse_gpu.reshape(-1)[torch.from_numpy(rows).to(lse_gpu.device)].cpu().numpy()
+    fin = np.isfinite(ref_lse)
+    np.testing.assert_array_equal(np.isfinite(lse), fin)
+    np.testing.assert_allclose(lse[fin], ref_lse[fin], rtol=0, atol=2e-3 if cfg.dtype == "bf16" else 1e-4)
+    return float(err.max()), float(err.mean())
+
+
+def run_prefill_config(oracle, name, alphas=None, per_head=6, all_rows=False):
+    cfg = inputs.CONFIGS[name]
+    print(f"[{name}] generating inputs", flush=True)
+    q, k, v, _ = inputs.make_inputs(cfg)
+    pipe = Pipeline(q, k, v, cfg.w, cfg.dtype)
+    print(f"[{name}] oracle score", flush=True)
+    sc_ref = oracle.score(q[:, :, -cfg.w:], k)
+    sc_gpu_dev = pipe.score()
+    sc_gpu = host(sc_gpu_dev)
+    check_scores(sc_gpu, sc_ref, cfg.w)
+    rng = np.random.default_rng(cfg.seed)
+    rows = None if all_rows else sample_rows(cfg, per_head, rng)
+    for alpha in (alphas or [cfg.alpha]):
+        print(f"[{name}] alpha={alpha}: select", flush=True)
+        sel_ref = oracle.select(sc_ref, cfg.n_hat, alpha)
+        sel_dev = pipe.select(sc_gpu_dev, alpha, accounted=False)
+        sel_gpu = host(sel_dev)
+        tolerated = check_selection(sel_gpu, sel_ref, sc_ref)
+        cells = metrics.selection_cells(cfg.n, cfg.n_hat, sel_gpu)
+        dens = cells.sum() / (cfg.B * cfg.Hq * metrics.causal_cells(cfg.n, cfg.n_hat))
+        print(f"[{name}] alpha={alpha}: density {dens:.4f}, lines at threshold tolerated: {tolerated}", flush=True)
+        out, lse = pipe.prefill(sel_dev)
+        torch.cuda.synchronize()
+        rr = rows if rows is not None else np.arange(cfg.B * cfg.Hq * cfg.n_hat, dtype=np.int64)
+        mx, mean = check_attention(oracle, cfg, q, k, v, sel_gpu, out, lse, rr, mode=0 if all_rows else 1)
+        print(f"[{name}] alpha={alpha}: attention max-abs {mx:.2e} mean-abs {mean:.2e} on {len(rr)} rows", flush=True)
+    return cfg, q, k, v, pipe
+
+
+def test_config1_tiny(oracle):
+    run_prefill_config(oracle, "tiny", all_rows=True)
+
+
+def test_config2_llama8b_8k(oracle):
+    run_prefill_config(oracle, "llama8b_8k", per_head=8)
+
+
+def test_config3_multiturn_32k(oracle):
+    run_prefill_config(oracle, "multiturn_32k", per_head=6)
+
+
+def test_config4_stress_131k(oracle):
+    run_prefill_config(oracle, "stress_131k", alphas=[0.90, 0.95, 0.98], per_head=2)
+
+
+def test_config5_llama70b_decode_compress(oracle):
+    """Batch-4 prefill, then 256 decode steps with the cache re-scored every 16 generated tokens
+    from the last 16 query vectors (first re-selection after 16 tokens, Sec. 5.2), 2048 kept per KV head."""
+    cfg, q, k, v, pipe = run_prefill_config(oracle, "llama70b_16k_b4", per_head=1)
+    steps, n_d, budget = 256, 16, 2048
+    dq, dk, dv = inputs.make_decode_step(cfg, steps)
+    from tests.gpu_util import to_dev
+    from paper_2507_13681_amd import binding
+    cap = cfg.n + steps
+    Kc = torch.empty((cfg.B, cfg.Hkv, cap, cfg.d), dtype=torch.bfloat16, device="cuda")
+    Vc = torch.empty_like(Kc)
+    Kc[:, :, :cfg.n] = pipe.k; Vc[:, :, :cfg.n] = pipe.v
+    Kc[:, :, cfg.n:] = to_dev(dk, "bf16"); Vc[:, :, cfg.n:] = to_dev(dv, "bf16")
+    dqd = to_dev(dq, "bf16")
+    kfull = np.concatenate([k, dk], axis=2)
+    del pipe
+    ctx = binding.Context(binding.make_shape(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cap, 1, n_d, "bf16"), budget)
+    keep_idx = torch.empty((cfg.B, cfg.Hkv, budget), dtype=torch.int32, device="cuda")
+    keep_cnt = torch.empty((cfg.B, cfg.Hkv), dtype=torch.int32, device="cuda")
+    checked = 0
+    for call in range(1, steps // n_d + 1):
+        ln = cfg.n + n_d * call                      # cache length after 16*call generated tokens
+        shape = binding.make_shape(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, ln, 1, n_d, "bf16")
+        k_now = Kc[:, :, :ln].contiguous()
+        q_obs = dqd[:, :, n_d * (call - 1):n_d * call].contiguous()
+        ctx.ls_kv_compress(shape, budget, q_obs, k_now, None, keep_idx, keep_cnt)
+        if call in (1, 8, 16):                       # the oracle is run on three of the 16 calls
+            print(f"[llama70b_16k_b4] compress call {call}, cache length {ln}", flush=True)
+            score = torch.empty((cfg.B, cfg.Hkv, ln), dtype=torch.float32, device="cuda")
+            ctx.debug_compress_score(shape, score)
+            score = score.cpu().numpy()
+            ref = oracle.compress(dq[:, :, n_d * (call - 1):n_d * call], kfull[:, :, :ln], budget)
+            np.testing.assert_allclose(score, ref["score"], rtol=1e-3, atol=1e-6 * n_d)
+            ki = keep_idx.cpu().numpy()
+            assert np.all(keep_cnt.cpu().numpy() == budget)
+            for b in range(cfg.B):
+                for j in range(cfg.Hkv):
+                    got = ki[b, j]
+                    np.testing.assert_array_equal(got, oracle.topb(score[b, j], budget))
+                    diff = np.setxor1d(got, ref["keep_idx"][b, j])
+                    if len(diff):
+                        thr = np.sort(ref["score"][b, j])[::-1][budget - 1]
+                        assert np.all(np.abs(ref["score"][b, j][diff] - thr) <= 1e-3 * thr)
+            checked += 1
+    assert checked == 3
