@@ -3,8 +3,11 @@ configuration bench.py times: score -> select -> sparse prefill (-> KV retention
 workload) through the C ABI, against the CPU oracle.
 
   * line weights: every entry compared (rel 1e-3, abs 1e-6 * w);
-  * selected sets: must equal the oracle's, except for lines whose weight lies within 1e-3
-    (relative) of that list's selection threshold;
+  * selected sets: must equal the oracle's, except for lines at the selection threshold: either
+    their weight lies within 1e-3 (relative) of the lightest selected weight of that list (order
+    ambiguity), or all differing lines together weigh less than 1e-3 of the coverage threshold
+    alpha * total (stop ambiguity: the loop's exit test `sum >= alpha * total` flips one line
+    earlier or later when the running sums differ in the last bits);
   * attention outputs: compared on sampled rows (all rows for the tiny workload) against the
     oracle evaluated on the device's own index sets: max-abs <= 2e-2, mean-abs <= 5e-3 for bf16,
     1e-4 for fp32.
@@ -26,7 +29,7 @@ def check_scores(gpu, ref, w):
     np.testing.assert_allclose(gpu["total"], ref["total"], rtol=1e-5)
 
 
-def check_selection(gpu, ref, sc_ref, tol=1e-3):
+def check_selection(gpu, ref, sc_ref, alpha, tol=1e-3):
     """Sets equal up to lines at the selection threshold.  Returns the number of tolerated lines."""
     B, Hq = ref["v_cnt"].shape
     tolerated = 0
@@ -43,8 +46,11 @@ def check_selection(gpu, ref, sc_ref, tol=1e-3):
                 # (or of the heaviest line when it selected none)
                 thr = wts[r].min() if len(r) else wts.max()
                 bad = np.abs(wts[diff] - thr) > tol * max(thr, 1e-30)
+                mass = float(wts[diff].astype(np.float64).sum())
+                if mass <= tol * alpha * float(sc_ref["total"][b, h]):
+                    bad[:] = False
                 assert not bad.any(), (f"b={b} h={h} {wname}: {bad.sum()} of {len(diff)} differing lines are not at the "
-                                       f"threshold {thr:.3e} (gpu {len(g)} lines, oracle {len(r)})")
+                                       f"threshold {thr:.3e} (gpu {len(g)} lines, oracle {len(r)}, mass {mass:.3e})")
                 tolerated += len(diff)
     return tolerated
 
@@ -96,7 +102,7 @@ def run_prefill_config(oracle, name, alphas=None, per_head=6, all_rows=False):
         sel_ref = oracle.select(sc_ref, cfg.n_hat, alpha)
         sel_dev = pipe.select(sc_gpu_dev, alpha, accounted=False)
         sel_gpu = host(sel_dev)
-        tolerated = check_selection(sel_gpu, sel_ref, sc_ref)
+        tolerated = check_selection(sel_gpu, sel_ref, sc_ref, alpha)
         cells = metrics.selection_cells(cfg.n, cfg.n_hat, sel_gpu)
         dens = cells.sum() / (cfg.B * cfg.Hq * metrics.causal_cells(cfg.n, cfg.n_hat))
         print(f"[{name}] alpha={alpha}: density {dens:.4f}, lines at threshold tolerated: {tolerated}", flush=True)
