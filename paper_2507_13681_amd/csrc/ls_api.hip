@@ -85,7 +85,7 @@ inline int words_of(int64_t n) { return (int)((n + 31) / 32) + 8; }
 inline int tab_len_of(int64_t n) { return (int)(n / 64) + 4; }
 size_t ws_prefill(const ls_shape* s) {
     const size_t BH = (size_t)s->B * s->Hq;
-    return 2 * up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n));
+    return up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH);
 }
 size_t ws_compress(const ls_shape* s) {
     return ws_score(s, false) + up((size_t)s->B * s->Hkv * (size_t)s->n * 4);
@@ -204,13 +204,13 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
         return fail(c, LS_ESHAPE, "ls_sparse_prefill: n too large for the LDS bitmaps");
     Bump bp{c->ws, c->ws_bytes, 0};
     uint32_t* obits = bp.take<uint32_t>((size_t)BH * words);
-    uint32_t* vbits = bp.take<uint32_t>((size_t)BH * words);
+    uint8_t* hflag = bp.take<uint8_t>((size_t)BH);
     uint8_t* tab = bp.take<uint8_t>((size_t)BH * tab_len);
     if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_sparse_prefill: workspace of %zu bytes is too small", c->ws_bytes);
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: hipSetDevice failed");
     ls::PlanArgs p{};
     p.n = s->n; p.words = words; p.tab_len = tab_len; p.v_idx = v_idx; p.v_cnt = v_cnt; p.s_idx = s_idx; p.s_cnt = s_cnt;
-    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.vbits = vbits; p.tab = tab;
+    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.tab = tab; p.hflag = hflag;
     hipError_t e = ls::launch_plan(p, BH, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(plan): %s", hipGetErrorString(e));
     ls::PrefillArgs a{};
@@ -219,7 +219,7 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     a.Hq = s->Hq; a.Hkv = s->Hkv; a.G = s->Hq / s->Hkv; a.BH = BH;
     a.nqb = (int)((s->n - a.pos0 + 127) / 128);
     a.words = words; a.tab_len = tab_len; a.scale_log2e = scale_log2e(s);
-    a.obits = obits; a.vbits = vbits; a.tab = tab; a.v_idx = v_idx; a.v_cnt = v_cnt; a.cap_v = cap_v;
+    a.obits = obits; a.tab = tab; a.hflag = hflag; a.v_idx = v_idx; a.v_cnt = v_cnt; a.cap_v = cap_v;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (c->profile) {
         if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)

@@ -69,11 +69,9 @@ __device__ __forceinline__ float bf2f(uint16_t b) {
 
 // Pack 8 probabilities into a fragment (operand of the P*V product).
 __device__ __forceinline__ void pack_frag(Frag<bf16_t>& f, const float* p) {
-    uint32_t w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(p[2 * i]) | ((uint32_t)f2bf(p[2 * i + 1]) << 16);
-    struct U4 { uint32_t a, b, c, d; } u = {w[0], w[1], w[2], w[3]};
-    f.v = __builtin_bit_cast(bf16x8, u);
+    typedef __attribute__((ext_vector_type(8))) float f32x8;
+    const f32x8 x = {p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]};
+    f.v = __builtin_convertvector(x, bf16x8);          // v_cvt_pk_bf16_f32, round to nearest even
 }
 __device__ __forceinline__ void pack_frag(Frag<float>& f, const float* p) {
 #pragma unroll

@@ -45,8 +45,9 @@ struct PlanArgs {
     int words, tab_len;
     const int32_t *v_idx, *v_cnt, *s_idx, *s_cnt;
     int cap_v, cap_s;
-    uint32_t *obits, *vbits;  // [BH][words]
+    uint32_t* obits;          // [BH][words]
     uint8_t* tab;             // [BH][tab_len]
+    uint8_t* hflag;           // [BH]
 };
 
 struct PrefillArgs {
@@ -56,8 +57,8 @@ struct PrefillArgs {
     int64_t n, n_hat, pos0;
     int Hq, Hkv, G, BH, nqb, words, tab_len;
     float scale_log2e;
-    const uint32_t *obits, *vbits;
-    const uint8_t* tab;
+    const uint32_t* obits;
+    const uint8_t *tab, *hflag;
     const int32_t *v_idx, *v_cnt;
     int cap_v;
 };

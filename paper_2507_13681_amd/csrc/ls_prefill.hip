@@ -12,9 +12,10 @@
 // per-head table built by plan_kernel says, for each j, whether any (or every) diagonal in that range
 // is selected.
 //   phase 1: key blocks whose diagonal range holds a selected diagonal are streamed as contiguous
-//            64-key tiles; the cell mask is (diagonal bit | column bit), read from bitmaps in LDS.
-//   phase 2: selected columns that lie in key blocks phase 1 skipped are gathered, 64 at a time,
-//            into packed tiles (only the causal test remains).
+//            64-key tiles; the cell mask is the diagonal bit, read from a bitmap in LDS.
+//   phase 2: the selected columns (up to the block's last row) are gathered, 64 at a time, into
+//            packed tiles; a cell is dropped there if its diagonal is selected (phase 1 counted it),
+//            which the per-j table decides for whole columns in the common cases.
 // So every allowed cell is visited exactly once.  Each wave owns 32 rows and skips the 32 x 32
 // sub-tiles in which none of its rows has an allowed cell.
 //
@@ -30,41 +31,32 @@ constexpr int BN = 64;    // keys per tile
 constexpr int PREFILL_THREADS = 256;
 
 // ---------------------------------------------------------------------------------------------
-// plan: per (batch, head) bitmaps of selected diagonals / columns and the per-j activity table.
-//   obits, vbits : [BH][words] uint32, bit i of word i/32; words = n/32 rounded up + 8 zero words
-//   tab          : [BH][tab_len] bytes, entry j+1 for j = -1 .. ; bit0 = some diagonal of
-//                  [64j-63, 64j+127] is selected, bit1 = all of them are (and 64j-63 >= 0).
+// plan: per (batch, head) bitmap of the selected diagonals, the per-j activity table, a head flag.
+//   obits : [BH][words] uint32, bit o of word o/32; words = n/32 rounded up + 8 zero words
+//   tab   : [BH][tab_len] bytes, entry j+1 for j = -1 .. ; bit0 = some diagonal of
+//           [64j-63, 64j+127] is selected, bit1 = all of them are (and none is cut off at 0 or n-1)
+//   hflag : [BH] bytes, bit0 = every diagonal 0..n-1 is selected (the mask is plain causal)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     extern __shared__ uint32_t sm[];
+    __shared__ int total_bits;
     const int bh = blockIdx.x;
     const int64_t n = a.n;
     const int words = a.words;
     const int tid = threadIdx.x;
     int ns = a.s_cnt[bh]; if (ns > a.cap_s) ns = a.cap_s; if (ns < 0) ns = 0;
-    int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
     const int32_t* si = a.s_idx + (int64_t)bh * a.cap_s;
-    const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
-
-    // selected columns -> bitmap
     for (int i = tid; i < words; i += blockDim.x) sm[i] = 0u;
-    __syncthreads();
-    for (int i = tid; i < nv; i += blockDim.x) {
-        const int32_t c = vi[i];
-        if (c >= 0 && c < n) atomicOr(&sm[c >> 5], 1u << (c & 31));
-    }
-    __syncthreads();
-    for (int i = tid; i < words; i += blockDim.x) a.vbits[(int64_t)bh * words + i] = sm[i];
-    __syncthreads();
-    // selected diagonals -> bitmap
-    for (int i = tid; i < words; i += blockDim.x) sm[i] = 0u;
+    if (tid == 0) total_bits = 0;
     __syncthreads();
     for (int i = tid; i < ns; i += blockDim.x) {
         const int32_t o = si[i];
         if (o >= 0 && o < n) atomicOr(&sm[o >> 5], 1u << (o & 31));
     }
     __syncthreads();
-    for (int i = tid; i < words; i += blockDim.x) a.obits[(int64_t)bh * words + i] = sm[i];
+    int mine = 0;
+    for (int i = tid; i < words; i += blockDim.x) { a.obits[(int64_t)bh * words + i] = sm[i]; mine += __popc(sm[i]); }
+    atomicAdd(&total_bits, mine);
     // activity table
     for (int e = tid; e < a.tab_len; e += blockDim.x) {
         const int64_t j = (int64_t)e - 1;
@@ -87,6 +79,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
         if (!cut && hi >= lo && cnt == (int)(hi - lo + 1) && hi == 64 * j + 127) f |= 2;
         a.tab[(int64_t)bh * a.tab_len + e] = f;
     }
+    __syncthreads();
+    if (tid == 0) a.hflag[bh] = (total_bits == (int)n) ? 1 : 0;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -97,6 +91,7 @@ struct TileCfg {
     static constexpr int EB = Elem<T>::bytes;
     static constexpr int EPC = Elem<T>::per16;            // elements per 16-byte chunk
     static constexpr int CPR = D / EPC;                   // 16-byte chunks per K/V row
+    static constexpr int CPT = CPR / 4;                   // chunks each thread moves per tile and operand
     static constexpr int K_STRIDE = D * EB + 16;          // bytes per staged K row
     static constexpr int VT_STRIDE = BN * EB + 16;        // bytes per staged V^T row
     static constexpr int K_BYTES = BN * K_STRIDE;
@@ -146,16 +141,20 @@ __device__ __forceinline__ uint32_t window32(const uint32_t* bits, int64_t base)
     return (uint32_t)(x >> sh);
 }
 
+// Tile sequence of one workgroup: first the n1 key blocks crossed by a selected diagonal (ascending),
+// then n2 packed tiles of 64 selected columns each.  K/V rows of tile t+1 are fetched into registers
+// while tile t is multiplied out of LDS buffer t&1, then written to buffer (t+1)&1; one barrier per tile.
 template <typename T, int D>
-__global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a) {
+__global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs a) {
     using C = TileCfg<T, D>;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* k_lds = smem;
-    unsigned char* vt_lds = smem + C::K_BYTES;
-    uint32_t* ob = reinterpret_cast<uint32_t*>(smem + C::K_BYTES + C::VT_BYTES);
-    uint32_t* vb = ob + a.words;
-    int32_t* colbuf = reinterpret_cast<int32_t*>(vb + a.words);          // 128 entries
-    uint8_t* tab = reinterpret_cast<uint8_t*>(colbuf + 128);             // tab_len entries
+    unsigned char* k_lds = smem;                                         // [2][K_BYTES]
+    unsigned char* vt_lds = smem + 2 * C::K_BYTES;                       // [2][VT_BYTES]
+    uint32_t* ob = reinterpret_cast<uint32_t*>(smem + 2 * C::K_BYTES + 2 * C::VT_BYTES);
+    int32_t* colring = reinterpret_cast<int32_t*>(ob + a.words);         // [2][64]
+    int32_t* wcnt = colring + 128;                                       // [8]
+    uint16_t* kbl = reinterpret_cast<uint16_t*>(wcnt + 8);               // [tab_len] active key blocks
+    uint8_t* tab = reinterpret_cast<uint8_t*>(kbl + ((a.tab_len + 7) & ~7));
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r32 = lane & 31, g = lane >> 5;
@@ -182,11 +181,8 @@ __global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a)
     const T* Vg = reinterpret_cast<const T*>(a.v) + ((int64_t)b * a.Hkv + kvh) * n * D;
     const T* Qg = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.n_hat * D;
 
-    // bitmaps and activity table of this head -> LDS
-    for (int i = tid; i < a.words; i += PREFILL_THREADS) {
-        ob[i] = a.obits[(int64_t)bh * a.words + i];
-        vb[i] = a.vbits[(int64_t)bh * a.words + i];
-    }
+    // diagonal bitmap and activity table of this head -> LDS
+    for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i] = a.obits[(int64_t)bh * a.words + i];
     for (int i = tid; i < a.tab_len; i += PREFILL_THREADS) tab[i] = a.tab[(int64_t)bh * a.tab_len + i];
 
     // this lane's query row and its fragments
@@ -201,19 +197,46 @@ __global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a)
 #pragma unroll
         for (int c = 0; c < C::KSTEPS; ++c) zero_frag(qf[c]);
     }
+    __syncthreads();
+
+    // ---- ordered list of the key blocks phase 1 visits
+    const int64_t jb = blockpos / BN;                      // even
+    const int kb_hi = (int)(posmax / BN);
+    int n1 = 0;
+    for (int base = 0; base <= kb_hi; base += PREFILL_THREADS) {
+        const int kb = base + tid;
+        const bool act = kb <= kb_hi && (tab[jb - kb + 1] & 1);
+        const uint64_t bal = __ballot(act);
+        if (lane == 0) wcnt[wv] = __popcll(bal);
+        __syncthreads();
+        int off = n1;
+        for (int w2 = 0; w2 < wv; ++w2) off += wcnt[w2];
+        if (act) kbl[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)kb;
+        n1 += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        __syncthreads();
+    }
+    // ---- how many selected columns phase 2 gathers (columns beyond the block's last row are invisible)
+    int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
+    const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
+    if (a.hflag[bh] & 1) nv = 0;                           // every diagonal is selected: phase 1 covers all cells
+    if (nv > 0 && (int64_t)vi[nv - 1] > posmax) {          // ascending list: binary search for the first column > posmax
+        int lo = 0, hi = nv - 1;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if ((int64_t)vi[mid] > posmax) hi = mid; else lo = mid + 1; }
+        nv = lo;
+    }
+    const int n2 = (nv + BN - 1) / BN;
+    const int ntiles = n1 + n2;
 
     f32x16 oacc[C::DBLK];
 #pragma unroll
     for (int i = 0; i < C::DBLK; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;                  // m_run in raw logit units
     const float sc2 = a.scale_log2e;
 
-    __syncthreads();
-
-    // ---- one staged tile: masks am[0], am[1] say which of the 2 x 32 keys this lane's row may see
-    auto process = [&](uint32_t am0, uint32_t am1) {
+    // ---- one staged tile: masks am0 / am1 say which of the 2 x 32 keys this lane's row may see
+    auto process = [&](const unsigned char* kt, const unsigned char* vt, uint32_t am0, uint32_t am1, bool full) {
         f32x16 s[2];
         bool act[2];
         act[0] = __ballot(am0 != 0u) != 0ull;
@@ -224,7 +247,7 @@ __global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
             if (act[sub]) {
-                const unsigned char* krow = k_lds + (32 * sub + r32) * C::K_STRIDE + 8 * g * C::EB;
+                const unsigned char* krow = kt + (32 * sub + r32) * C::K_STRIDE + 8 * g * C::EB;
 #pragma unroll
                 for (int c = 0; c < C::KSTEPS; ++c) {
                     Frag<T> kf;
@@ -234,28 +257,36 @@ __global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a)
             }
         }
         float mx = -INFINITY;
+        if (full) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const uint32_t am = sub ? am1 : am0;
+            for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kb = 8 * (r >> 2) + 4 * g + (r & 3);
-                const float x = ((am >> kb) & 1u) ? s[sub][r] * sc2 : -INFINITY;
-                s[sub][r] = x;
-                mx = fmaxf(mx, x);
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const uint32_t am = sub ? am1 : am0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kbit = 8 * (r >> 2) + 4 * g + (r & 3);
+                    const float x = ((am >> kbit) & 1u) ? s[sub][r] : -INFINITY;
+                    s[sub][r] = x;
+                    mx = fmaxf(mx, x);
+                }
             }
         }
         mx = fmaxf(mx, xor32(mx));
         const float m_new = fmaxf(m_run, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float corr = fast_exp2(m_run - m_safe);
+        const float corr = fast_exp2((m_run - m_safe) * sc2);
+        const float mneg = -m_safe * sc2;
         m_run = m_new;
         float psum = 0.f;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(s[sub][r] - m_safe);
+                const float p = fast_exp2(__builtin_fmaf(s[sub][r], sc2, mneg));
                 s[sub][r] = p;
                 psum += p;
             }
@@ -279,115 +310,114 @@ __global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a)
 #pragma unroll
                 for (int i = 0; i < C::DBLK; ++i) {
                     Frag<T> vf;
-                    load_frag(vf, vt_lds + (32 * i + r32) * C::VT_STRIDE + (32 * sub + 16 * hh + 8 * g) * C::EB);
+                    load_frag(vf, vt + (32 * i + r32) * C::VT_STRIDE + (32 * sub + 16 * hh + 8 * g) * C::EB);
                     mma(oacc[i], vf, pf);          // O^T[d][row] += V^T[d][key] P^T[key][row]
                 }
             }
         }
     };
 
-    // ---- stage 64 rows of K and V into LDS; row id < 0 means "no such row" (zero fill)
-    auto stage = [&](auto row_of) {
-        // K: 16 lanes cover one row
-        for (int id = tid; id < BN * C::CPR; id += PREFILL_THREADS) {
-            const int r = id / C::CPR, c = id % C::CPR;
-            const int64_t gr = row_of(r);
-            f32x4 raw = {0.f, 0.f, 0.f, 0.f};
-            if (gr >= 0) raw = *reinterpret_cast<const f32x4*>(reinterpret_cast<const unsigned char*>(Kg + gr * D) + 16 * c);
-            *reinterpret_cast<f32x4*>(k_lds + r * C::K_STRIDE + 16 * c) = raw;
-        }
-        // V: one lane per key row, transposed into LDS
-        {
-            const int r = tid & 63, cg = tid >> 6;
-            const int64_t gr = row_of(r);
-            const int col = vt_col(r);
-#pragma unroll
-            for (int cc = 0; cc < C::CPR / 4; ++cc) {
-                const int c = cg * (C::CPR / 4) + cc;
-                f32x4 raw = {0.f, 0.f, 0.f, 0.f};
-                if (gr >= 0) raw = *reinterpret_cast<const f32x4*>(reinterpret_cast<const unsigned char*>(Vg + gr * D) + 16 * c);
-                store_vt<T>(vt_lds, C::VT_STRIDE, c * C::EPC, col, raw);
-            }
+    // ---- staging: thread -> (row tid/4, chunks tid%4 + 4i) for K, (row tid%64, chunks (tid/64)*CPT + i) for V
+    const int rk = tid >> 2, ck0 = tid & 3;
+    const int rv = tid & 63, cv0 = (tid >> 6) * C::CPT;
+    const int vcol = vt_col(rv);
+    f32x4 kreg[C::CPT], vreg[C::CPT];
+    int32_t colk = -1, colv = -1;                          // gathered rows of the tile being fetched
+
+    // global row feeding slot r of tile t (or -1): contiguous tiles read key block kbl[t]
+    auto src_row = [&](int t, int r, int32_t gathered) -> int64_t {
+        if (t < n1) { const int64_t kr = (int64_t)kbl[t] * BN + r; return kr < n ? kr : -1; }
+        return gathered;
+    };
+    auto load_cols = [&](int t) {                          // column indices of gathered tile t -> registers
+        colk = -1; colv = -1;
+        if (t >= n1 && t < ntiles) {
+            const int base = (t - n1) * BN;
+            if (base + rk < nv) colk = vi[base + rk];
+            if (base + rv < nv) colv = vi[base + rv];
         }
     };
-
-    // ================= phase 1: key blocks crossed by a selected diagonal =================
-    const int64_t jb = blockpos / BN;                      // even
-    const int64_t kb_hi = posmax / BN;
-    for (int64_t kb = 0; kb <= kb_hi; ++kb) {
-        const int64_t j = jb - kb;                         // >= -1
-        const uint8_t f = tab[j + 1];
-        if (!(f & 1)) continue;
-        const int64_t key0 = kb * BN;
-        __syncthreads();                                   // previous tile fully consumed
-        stage([&](int r) -> int64_t { const int64_t kr = key0 + r; return kr < n ? kr : -1; });
-        __syncthreads();
-        uint32_t am0, am1;
-        if (!row_ok) { am0 = am1 = 0u; }
-        else if (f & 2) { am0 = am1 = 0xFFFFFFFFu; }
-        else {
-            // bit i of the mask <-> key key0 + 32*sub + i <-> diagonal pos - key
-            const int64_t d0 = pos - key0;                 // diagonal of the tile's first key
-            am0 = __brev(window32(ob, d0 - 31));
-            am1 = __brev(window32(ob, d0 - 63));
-            // selected columns, limited to keys <= pos
-            uint32_t c0 = vb[(key0 >> 5)], c1 = vb[(key0 >> 5) + 1];
-            if (d0 < 31) c0 = (d0 < 0) ? 0u : (c0 & (0xFFFFFFFFu >> (31 - (int)d0)));
-            if (d0 < 63) c1 = (d0 < 32) ? 0u : (c1 & (0xFFFFFFFFu >> (63 - (int)d0)));
-            am0 |= c0; am1 |= c1;
+    auto fetch = [&](int t) {                              // global -> registers
+        const int64_t gk = src_row(t, rk, colk), gv = src_row(t, rv, colv);
+#pragma unroll
+        for (int i = 0; i < C::CPT; ++i) {
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            kreg[i] = z; vreg[i] = z;
+            if (gk >= 0) kreg[i] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const unsigned char*>(Kg + gk * D) + 16 * (ck0 + 4 * i));
+            if (gv >= 0) vreg[i] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const unsigned char*>(Vg + gv * D) + 16 * (cv0 + i));
         }
-        process(am0, am1);
-    }
+    };
+    auto stash = [&](int t) {                              // registers -> LDS buffer t & 1 (+ column ids)
+        unsigned char* kt = k_lds + (t & 1) * C::K_BYTES;
+        unsigned char* vt = vt_lds + (t & 1) * C::VT_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::CPT; ++i) {
+            *reinterpret_cast<f32x4*>(kt + rk * C::K_STRIDE + 16 * (ck0 + 4 * i)) = kreg[i];
+            store_vt<T>(vt, C::VT_STRIDE, (cv0 + i) * C::EPC, vcol, vreg[i]);
+        }
+        if (t >= n1 && tid < BN) colring[(t & 1) * BN + tid] = colv;
+    };
 
-    // ================= phase 2: selected columns outside those key blocks =================
-    {
-        int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
-        const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
-        int cur = 0, fill = 0;
-        bool more = nv > 0;
-        while (true) {
-            // refill the column buffer (every wave computes the same thing; wave 0 writes)
-            while (more && fill < BN) {
-                const int i = cur + lane;
-                int32_t col = (i < nv) ? vi[i] : 0x7FFFFFFF;
-                const bool inrange = (i < nv) && (col >= 0) && ((int64_t)col <= posmax);
-                bool keep = false;
-                if (inrange) keep = !(tab[jb - (col >> 6) + 1] & 1);
-                const uint64_t km = __ballot(keep);
-                if (keep && wv == 0) colbuf[fill + __popcll(km & ((1ull << lane) - 1ull))] = col;
-                fill += __popcll(km);
-                cur += 64;
-                // the list is ascending: once an entry lies beyond the block's last row, nothing follows
-                const uint64_t beyond = __ballot((i < nv) && ((int64_t)col > posmax));
-                if (cur >= nv || beyond != 0ull) more = false;
+    if (ntiles > 0) {
+        load_cols(0);
+        fetch(0);
+        stash(0);
+        load_cols(1);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const bool more = t + 1 < ntiles;
+        if (more) fetch(t + 1);                            // uses the columns loaded one iteration ago
+        const int32_t colv_next = colv;
+        if (more) load_cols(t + 2);
+        // ---- masks of tile t
+        uint32_t am0 = 0u, am1 = 0u;
+        bool full = false;
+        if (t < n1) {
+            const int64_t key0 = (int64_t)kbl[t] * BN;
+            const uint8_t f = tab[jb - kbl[t] + 1];
+            if (!row_ok) { am0 = am1 = 0u; }
+            else if (f & 2) { am0 = am1 = 0xFFFFFFFFu; }
+            else {
+                // bit i of the mask <-> key key0 + 32*sub + i <-> diagonal pos - key
+                const int64_t d0 = pos - key0;             // diagonal of the tile's first key
+                am0 = __brev(window32(ob, d0 - 31));
+                am1 = __brev(window32(ob, d0 - 63));
             }
-            if (fill == 0) break;
-            const int cnt = fill < BN ? fill : BN;
-            __syncthreads();                               // colbuf visible; previous tile consumed
-            stage([&](int r) -> int64_t { return r < cnt ? (int64_t)colbuf[r] : -1; });
-            // causal mask: columns are ascending, so the visible ones form a prefix
-            uint32_t am0 = 0u, am1 = 0u;
+            full = (f & 2) && (__ballot(row_ok) == ~0ull);
+        } else {
+            const int32_t* cols = colring + (t & 1) * BN;
+            const int base = (t - n1) * BN;
+            const int cnt = nv - base < BN ? nv - base : BN;
+            // slot `lane`: is the column's key block crossed by selected diagonals for this row block?
+            const int32_t mycol = lane < cnt ? cols[lane] : 0;
+            const uint8_t f = lane < cnt ? tab[jb - (mycol >> 6) + 1] : (uint8_t)3;
+            const uint64_t drop = __ballot(f == 3);        // wholly covered by phase 1 (or no such slot)
+            const uint64_t chk = __ballot(f == 1);         // partly covered: test cell by cell
+            uint64_t am = 0ull;
             if (row_ok) {
-                if ((int64_t)colbuf[cnt - 1] <= pos) {
-                    am0 = cnt >= 32 ? 0xFFFFFFFFu : ((1u << cnt) - 1u);
-                    am1 = cnt >= 64 ? 0xFFFFFFFFu : (cnt > 32 ? ((1u << (cnt - 32)) - 1u) : 0u);
-                } else {
-                    for (int i = 0; i < cnt; ++i) {
-                        if ((int64_t)colbuf[i] <= pos) { if (i < 32) am0 |= 1u << i; else am1 |= 1u << (i - 32); }
-                    }
+                // causal: columns ascend, the visible ones form a prefix
+                if ((int64_t)cols[cnt - 1] <= pos) am = cnt >= 64 ? ~0ull : ((1ull << cnt) - 1ull);
+                else for (int i = 0; i < cnt; ++i) if ((int64_t)cols[i] <= pos) am |= 1ull << i;
+                am &= ~drop;
+                uint64_t todo = chk & am;
+                while (todo) {
+                    const int i = __ffsll((unsigned long long)todo) - 1;
+                    todo &= todo - 1;
+                    const int64_t o = pos - cols[i];       // >= 0 here
+                    if ((ob[o >> 5] >> (o & 31)) & 1u) am &= ~(1ull << i);   // cell already counted on its diagonal
                 }
             }
-            __syncthreads();
-            process(am0, am1);
-            __syncthreads();                               // all waves done with colbuf[0..63] and the tile
-            if (fill > BN) {
-                int32_t t = 0;
-                if (wv == 0 && lane < fill - BN) t = colbuf[BN + lane];
-                __builtin_amdgcn_wave_barrier();
-                if (wv == 0 && lane < fill - BN) colbuf[lane] = t;
-                fill -= BN;
-            } else fill = 0;
+            am0 = (uint32_t)am; am1 = (uint32_t)(am >> 32);
         }
+        process(k_lds + (t & 1) * C::K_BYTES, vt_lds + (t & 1) * C::VT_BYTES, am0, am1, full);
+        if (more) {
+            const int32_t keep = colv; colv = colv_next;   // stash() records the columns of tile t+1
+            stash(t + 1);
+            colv = keep;
+        }
+        __syncthreads();
     }
 
     // ================= epilogue =================
@@ -405,14 +435,20 @@ __global__ __launch_bounds__(PREFILL_THREADS) void prefill_kernel(PrefillArgs a)
             }
         if (a.lse && g == 0)
             a.lse[(int64_t)bh * a.n_hat + (pos - row0)] =
-                l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
+                l_tot > 0.f ? (m_run * sc2 + log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
     }
 }
 
 template <typename T, int D>
-static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
+static size_t prefill_smem_t(int words, int tab_len) {
     using C = TileCfg<T, D>;
-    const size_t smem = C::K_BYTES + C::VT_BYTES + 2 * (size_t)a.words * 4 + 128 * 4 + (size_t)a.tab_len;
+    return 2 * (size_t)C::K_BYTES + 2 * (size_t)C::VT_BYTES + (size_t)words * 4 + 128 * 4 + 8 * 4 +
+           (size_t)((tab_len + 7) & ~7) * 2 + (size_t)tab_len + 16;
+}
+
+template <typename T, int D>
+static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
+    const size_t smem = prefill_smem_t<T, D>(a.words, a.tab_len);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<T, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
@@ -421,12 +457,10 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
 }
 
 size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len) {
-    size_t tiles = 0;
-    if (dtype == 0 && d == 128) tiles = TileCfg<bf16_t, 128>::K_BYTES + TileCfg<bf16_t, 128>::VT_BYTES;
-    else if (dtype == 0 && d == 64) tiles = TileCfg<bf16_t, 64>::K_BYTES + TileCfg<bf16_t, 64>::VT_BYTES;
-    else if (dtype == 1 && d == 128) tiles = TileCfg<float, 128>::K_BYTES + TileCfg<float, 128>::VT_BYTES;
-    else tiles = TileCfg<float, 64>::K_BYTES + TileCfg<float, 64>::VT_BYTES;
-    return tiles + 2 * (size_t)words * 4 + 128 * 4 + (size_t)tab_len;
+    if (dtype == 0 && d == 128) return prefill_smem_t<bf16_t, 128>(words, tab_len);
+    if (dtype == 0 && d == 64) return prefill_smem_t<bf16_t, 64>(words, tab_len);
+    if (dtype == 1 && d == 128) return prefill_smem_t<float, 128>(words, tab_len);
+    return prefill_smem_t<float, 64>(words, tab_len);
 }
 
 hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st) {

@@ -129,65 +129,68 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_kernel(SelectArgs a) {
 
 // ---- the greedy loop ----------------------------------------------------------------------------
 constexpr int WALK_THREADS = 256;
-constexpr int WALK_CHUNK = 1024;
+constexpr int WALK_CHUNK = 2048;
 
-struct WalkState { int64_t is, iv; float ol_s, ol_v, sum; int done; };
+struct WalkState { int is, iv; float ol_s, ol_v, sum; int done; };
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
+// The whole workgroup copies a window of each list (starting at that list's head) into LDS; lane 0
+// then walks while both heads and their successors are inside the windows.  The walking lane keeps
+// the two heads and their successors in registers, so an LDS read is issued one step before its
+// value is needed.
 __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     __shared__ float cw[2][WALK_CHUNK], cm[2][WALK_CHUNK], cl[2][WALK_CHUNK];
     __shared__ WalkState st;
-    __shared__ int64_t cbase[2];
     const int bh = blockIdx.x, tid = threadIdx.x;
-    const int64_t n = a.n, nh = a.n_hat;
-    const int64_t seg_s = ((int64_t)0 * a.BH + bh) * n, seg_v = ((int64_t)1 * a.BH + bh) * n;
+    const int n = (int)a.n;
+    const int64_t nh = a.n_hat;
+    const int64_t seg_s = ((int64_t)0 * a.BH + bh) * a.n, seg_v = ((int64_t)1 * a.BH + bh) * a.n;
     const float* w_l[2] = {a.sorted_w + seg_s, a.sorted_w + seg_v};
     const float* m_l[2] = {a.sorted_m + seg_s, a.sorted_m + seg_v};
     const int32_t* i_l[2] = {a.sidx1 + seg_s, a.sidx1 + seg_v};
-    if (tid == 0) { st.is = 0; st.iv = 0; st.ol_s = 0.f; st.ol_v = 0.f; st.sum = 0.f; st.done = 0; cbase[0] = -WALK_CHUNK; cbase[1] = -WALK_CHUNK; }
+    if (tid == 0) { st.is = 0; st.iv = 0; st.ol_s = 0.f; st.ol_v = 0.f; st.sum = 0.f; st.done = 0; }
     __syncthreads();
     const float target = a.alpha * a.total[bh];
     const bool early = a.accounted == nullptr;
     while (true) {
-        // (re)load the chunk that holds each list's head
+        const int base_s = st.is, base_v = st.iv;          // windows start at the heads
         for (int l = 0; l < 2; ++l) {
-            const int64_t head = l == 0 ? st.is : st.iv;
-            const int64_t want = head / WALK_CHUNK * WALK_CHUNK;
-            if (want != cbase[l] && head < n) {
-                for (int i = tid; i < WALK_CHUNK; i += WALK_THREADS) {
-                    const int64_t gi = want + i;
-                    if (gi < n) {
-                        const int64_t x = i_l[l][gi];
-                        cw[l][i] = w_l[l][gi];
-                        cm[l][i] = m_l[l][gi];
-                        cl[l][i] = (float)((n - x) < nh ? (n - x) : nh);     // line length in the n_hat x n block
-                    }
+            const int base = l == 0 ? base_s : base_v;
+            for (int i = tid; i < WALK_CHUNK; i += WALK_THREADS) {
+                const int gi = base + i;
+                if (gi < n) {
+                    const int64_t x = i_l[l][gi];
+                    cw[l][i] = w_l[l][gi];
+                    cm[l][i] = m_l[l][gi];
+                    cl[l][i] = (float)((a.n - x) < nh ? (a.n - x) : nh);      // line length in the n_hat x n block
                 }
             }
         }
         __syncthreads();
         if (tid == 0) {
-            for (int l = 0; l < 2; ++l) {
-                const int64_t head = l == 0 ? st.is : st.iv;
-                if (head < n) cbase[l] = head / WALK_CHUNK * WALK_CHUNK;
-            }
-            int64_t is = st.is, iv = st.iv;
+            int is = base_s, iv = base_v;
             float ol_s = st.ol_s, ol_v = st.ol_v, sum = st.sum;
-            const int64_t end_s = (cbase[0] + WALK_CHUNK < n) ? cbase[0] + WALK_CHUNK : n;
-            const int64_t end_v = (cbase[1] + WALK_CHUNK < n) ? cbase[1] + WALK_CHUNK : n;
+            // last index each head may reach inside this window (its successor must be loaded too)
+            const int lim_s = (base_s + WALK_CHUNK >= n) ? n : base_s + WALK_CHUNK - 1;
+            const int lim_v = (base_v + WALK_CHUNK >= n) ? n : base_v + WALK_CHUNK - 1;
+            float ws = 0.f, ms = 0.f, ls = 0.f, wv = 0.f, mv = 0.f, lv = 0.f;          // heads
+            float ws2 = 0.f, ms2 = 0.f, ls2 = 0.f, wv2 = 0.f, mv2 = 0.f, lv2 = 0.f;    // successors
+            if (is < n) { ws = cw[0][0]; ms = cm[0][0]; ls = cl[0][0]; }
+            if (is + 1 < n) { ws2 = cw[0][1]; ms2 = cm[0][1]; ls2 = cl[0][1]; }
+            if (iv < n) { wv = cw[1][0]; mv = cm[1][0]; lv = cl[1][0]; }
+            if (iv + 1 < n) { wv2 = cw[1][1]; mv2 = cm[1][1]; lv2 = cl[1][1]; }
             int done = 0;
             while (true) {
                 if (!(sum < target) || (is >= n && iv >= n)) { done = 1; break; }
-                if ((is < n && is >= end_s) || (iv < n && iv >= end_v)) break;      // need another chunk
+                if ((is < n && is >= lim_s) || (iv < n && iv >= lim_v)) break;          // slide the windows
                 bool take_s;
-                float ds = 0.f, dv = 0.f;
-                if (is < n) ds = __fsub_rn(cw[0][is - cbase[0]], ol_v);
-                if (iv < n) dv = __fsub_rn(cw[1][iv - cbase[1]], ol_s);
+                const float ds = __fsub_rn(ws, ol_v);
+                const float dv = __fsub_rn(wv, ol_s);
                 if (iv >= n) take_s = true;
                 else if (is >= n) take_s = false;
                 else {
-                    float cs = __fsub_rn(cl[0][is - cbase[0]], (float)iv); if (cs < 1.0f) cs = 1.0f;
-                    float cv = __fsub_rn(cl[1][iv - cbase[1]], (float)is); if (cv < 1.0f) cv = 1.0f;
+                    float cs = __fsub_rn(ls, (float)iv); if (cs < 1.0f) cs = 1.0f;
+                    float cv = __fsub_rn(lv, (float)is); if (cv < 1.0f) cv = 1.0f;
                     take_s = __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
                 }
                 if (early) {
@@ -197,8 +200,17 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
                     const bool v_dead = (iv >= n) || !(dv > 0.f);
                     if (s_dead && v_dead) { is = n; iv = n; done = 1; break; }
                 }
-                if (take_s) { sum = __fadd_rn(sum, ds); ol_s = __fadd_rn(ol_s, cm[0][is - cbase[0]]); ++is; }
-                else        { sum = __fadd_rn(sum, dv); ol_v = __fadd_rn(ol_v, cm[1][iv - cbase[1]]); ++iv; }
+                if (take_s) {
+                    sum = __fadd_rn(sum, ds); ol_s = __fadd_rn(ol_s, ms); ++is;
+                    ws = ws2; ms = ms2; ls = ls2;
+                    const int j = is + 1 - base_s;
+                    if (is + 1 < n && j < WALK_CHUNK) { ws2 = cw[0][j]; ms2 = cm[0][j]; ls2 = cl[0][j]; }
+                } else {
+                    sum = __fadd_rn(sum, dv); ol_v = __fadd_rn(ol_v, mv); ++iv;
+                    wv = wv2; mv = mv2; lv = lv2;
+                    const int j = iv + 1 - base_v;
+                    if (iv + 1 < n && j < WALK_CHUNK) { wv2 = cw[1][j]; mv2 = cm[1][j]; lv2 = cl[1][j]; }
+                }
             }
             st.is = is; st.iv = iv; st.ol_s = ol_s; st.ol_v = ol_v; st.sum = sum; st.done = done;
         }
@@ -206,8 +218,8 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         if (st.done) break;
     }
     if (tid == 0) {
-        a.s_cnt[bh] = (int32_t)st.is;
-        a.v_cnt[bh] = (int32_t)st.iv;
+        a.s_cnt[bh] = st.is;
+        a.v_cnt[bh] = st.iv;
         if (a.accounted) a.accounted[bh] = st.sum;
     }
 }
