@@ -6,9 +6,9 @@
 //                 LDS histogram, and scatters its slice in order: inside a 64-element chunk the
 //                 rank among equal digits comes from wave ballots, across chunks from the wave's
 //                 running counters.  No atomics decide an output position.
-//   walk_kernel   one workgroup per head: the sequential greedy loop of Alg. 2, run by one lane in
-//                 binary32 with the operation order of the definition; the sorted lists are
-//                 streamed through LDS in chunks by the whole workgroup.
+//   walk_kernel   one wave per head: the greedy loop of Alg. 2 in binary32 with the operands and
+//                 operation order of the definition; runs of picks from one list are decided 64 at a
+//                 time by the lanes, the running sum is accumulated pick by pick.
 //   emit_kernel   one workgroup per (head, list): the chosen prefix of a sorted list becomes an
 //                 ascending index list (bitmap in LDS + prefix popcount).
 //   topb_kernel   Alg. 3: the `budget` largest scores per KV head by 4-pass radix select on the
@@ -128,99 +128,138 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_kernel(SelectArgs a) {
 }
 
 // ---- the greedy loop ----------------------------------------------------------------------------
-constexpr int WALK_THREADS = 256;
-constexpr int WALK_CHUNK = 2048;
-
-struct WalkState { int is, iv; float ol_s, ol_v, sum; int done; };
+// One wave per head.  The loop of Alg. 2 is sequential, but two things about it are not:
+//   * ol_s after k slashes were taken is the left-to-right binary32 sum of the first k maxima of
+//     the slash list, whatever the interleaving with verticals was (likewise ol_v), so both
+//     running overlaps are prefix arrays that can be filled ahead of the walk (still added one
+//     element after the other, so every value is the one the sequential loop would hold);
+//   * while the walk keeps taking from one list, the state of the other list is frozen, so the
+//     next 64 ratio tests can be evaluated by the 64 lanes at once; a ballot gives the length of
+//     the run of equal decisions.
+// What stays sequential is the accumulation of `sum` with its exit test after every pick: one
+// add and one compare per pick, on values already sitting in the lanes' registers.
+// Each pick therefore sees exactly the operands, operation order and roundings of the definition.
+constexpr int WALK_THREADS = 64;
+constexpr int WALK_WIN = 2048;                 // window of each list kept in LDS
+constexpr int WALK_LOOK = 64;                  // lookahead the run evaluation needs
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
-// The whole workgroup copies a window of each list (starting at that list's head) into LDS; lane 0
-// then walks while both heads and their successors are inside the windows.  The walking lane keeps
-// the two heads and their successors in registers, so an LDS read is issued one step before its
-// value is needed.
 __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
-    __shared__ float cw[2][WALK_CHUNK], cm[2][WALK_CHUNK], cl[2][WALK_CHUNK];
-    __shared__ WalkState st;
-    const int bh = blockIdx.x, tid = threadIdx.x;
+    __shared__ float cw[2][WALK_WIN], cl[2][WALK_WIN], cm[2][WALK_WIN];
+    __shared__ float pre[2][WALK_WIN + 1];     // pre[l][i]: overlap sum when base_l + i lines of list l are taken
+    const int bh = blockIdx.x, lane = threadIdx.x;
     const int n = (int)a.n;
     const int64_t nh = a.n_hat;
     const int64_t seg_s = ((int64_t)0 * a.BH + bh) * a.n, seg_v = ((int64_t)1 * a.BH + bh) * a.n;
     const float* w_l[2] = {a.sorted_w + seg_s, a.sorted_w + seg_v};
     const float* m_l[2] = {a.sorted_m + seg_s, a.sorted_m + seg_v};
     const int32_t* i_l[2] = {a.sidx1 + seg_s, a.sidx1 + seg_v};
-    if (tid == 0) { st.is = 0; st.iv = 0; st.ol_s = 0.f; st.ol_v = 0.f; st.sum = 0.f; st.done = 0; }
-    __syncthreads();
     const float target = a.alpha * a.total[bh];
     const bool early = a.accounted == nullptr;
-    while (true) {
-        const int base_s = st.is, base_v = st.iv;          // windows start at the heads
+
+    int head[2] = {0, 0};                      // is, iv
+    int base[2] = {0, 0};
+    float carry[2] = {0.f, 0.f};               // overlap sums at the window bases
+    bool need[2] = {true, true};
+    float sum = 0.f;
+    bool done = false;
+
+    while (!done) {
+        // ---- (re)fill the windows that ran low, then their overlap prefixes (lane l scans list l)
         for (int l = 0; l < 2; ++l) {
-            const int base = l == 0 ? base_s : base_v;
-            for (int i = tid; i < WALK_CHUNK; i += WALK_THREADS) {
-                const int gi = base + i;
+            if (!need[l]) continue;
+            base[l] = head[l];
+            for (int i = lane; i < WALK_WIN; i += WALK_THREADS) {
+                const int gi = base[l] + i;
+                float w = 0.f, m = 0.f, len = 1.f;
                 if (gi < n) {
                     const int64_t x = i_l[l][gi];
-                    cw[l][i] = w_l[l][gi];
-                    cm[l][i] = m_l[l][gi];
-                    cl[l][i] = (float)((a.n - x) < nh ? (a.n - x) : nh);      // line length in the n_hat x n block
+                    w = w_l[l][gi]; m = m_l[l][gi];
+                    len = (float)((a.n - x) < nh ? (a.n - x) : nh);       // line length in the n_hat x n block
                 }
+                cw[l][i] = w; cm[l][i] = m; cl[l][i] = len;
             }
         }
-        __syncthreads();
-        if (tid == 0) {
-            int is = base_s, iv = base_v;
-            float ol_s = st.ol_s, ol_v = st.ol_v, sum = st.sum;
-            // last index each head may reach inside this window (its successor must be loaded too)
-            const int lim_s = (base_s + WALK_CHUNK >= n) ? n : base_s + WALK_CHUNK - 1;
-            const int lim_v = (base_v + WALK_CHUNK >= n) ? n : base_v + WALK_CHUNK - 1;
-            float ws = 0.f, ms = 0.f, ls = 0.f, wv = 0.f, mv = 0.f, lv = 0.f;          // heads
-            float ws2 = 0.f, ms2 = 0.f, ls2 = 0.f, wv2 = 0.f, mv2 = 0.f, lv2 = 0.f;    // successors
-            if (is < n) { ws = cw[0][0]; ms = cm[0][0]; ls = cl[0][0]; }
-            if (is + 1 < n) { ws2 = cw[0][1]; ms2 = cm[0][1]; ls2 = cl[0][1]; }
-            if (iv < n) { wv = cw[1][0]; mv = cm[1][0]; lv = cl[1][0]; }
-            if (iv + 1 < n) { wv2 = cw[1][1]; mv2 = cm[1][1]; lv2 = cl[1][1]; }
-            int done = 0;
-            while (true) {
-                if (!(sum < target) || (is >= n && iv >= n)) { done = 1; break; }
-                if ((is < n && is >= lim_s) || (iv < n && iv >= lim_v)) break;          // slide the windows
-                bool take_s;
-                const float ds = __fsub_rn(ws, ol_v);
-                const float dv = __fsub_rn(wv, ol_s);
-                if (iv >= n) take_s = true;
-                else if (is >= n) take_s = false;
-                else {
-                    float cs = __fsub_rn(ls, (float)iv); if (cs < 1.0f) cs = 1.0f;
-                    float cv = __fsub_rn(lv, (float)is); if (cv < 1.0f) cv = 1.0f;
-                    take_s = __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
-                }
-                if (early) {
-                    // every later gain is <= the current head's (lists descend, overlaps only grow):
-                    // if no available head has a positive gain the sum can never reach the target
-                    const bool s_dead = (is >= n) || !(ds > 0.f);
-                    const bool v_dead = (iv >= n) || !(dv > 0.f);
-                    if (s_dead && v_dead) { is = n; iv = n; done = 1; break; }
-                }
-                if (take_s) {
-                    sum = __fadd_rn(sum, ds); ol_s = __fadd_rn(ol_s, ms); ++is;
-                    ws = ws2; ms = ms2; ls = ls2;
-                    const int j = is + 1 - base_s;
-                    if (is + 1 < n && j < WALK_CHUNK) { ws2 = cw[0][j]; ms2 = cm[0][j]; ls2 = cl[0][j]; }
-                } else {
-                    sum = __fadd_rn(sum, dv); ol_v = __fadd_rn(ol_v, mv); ++iv;
-                    wv = wv2; mv = mv2; lv = lv2;
-                    const int j = iv + 1 - base_v;
-                    if (iv + 1 < n && j < WALK_CHUNK) { wv2 = cw[1][j]; mv2 = cm[1][j]; lv2 = cl[1][j]; }
-                }
-            }
-            st.is = is; st.iv = iv; st.ol_s = ol_s; st.ol_v = ol_v; st.sum = sum; st.done = done;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < 2 && (lane == 0 ? need[0] : need[1])) {
+            float acc = lane == 0 ? carry[0] : carry[1];
+            const float* src = cm[lane];
+            float* dst = pre[lane];
+            for (int i = 0; i < WALK_WIN; ++i) { dst[i] = acc; acc = __fadd_rn(acc, src[i]); }
+            dst[WALK_WIN] = acc;
         }
-        __syncthreads();
-        if (st.done) break;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        need[0] = need[1] = false;
+
+        // ---- walk while both heads have WALK_LOOK entries of lookahead inside their windows
+        while (true) {
+            const int is = head[0], iv = head[1];
+            if (!(sum < target) || (is >= n && iv >= n)) { done = true; break; }
+            const bool low_s = is < n && is + WALK_LOOK > base[0] + WALK_WIN && base[0] + WALK_WIN < n;
+            const bool low_v = iv < n && iv + WALK_LOOK > base[1] + WALK_WIN && base[1] + WALK_WIN < n;
+            if (low_s || low_v) {
+                if (low_s) { need[0] = true; carry[0] = pre[0][is - base[0]]; }
+                if (low_v) { need[1] = true; carry[1] = pre[1][iv - base[1]]; }
+                break;
+            }
+            const bool s_has = is < n, v_has = iv < n;
+            // frozen heads of both lists
+            const float ws0 = s_has ? cw[0][is - base[0]] : 0.f, ls0 = s_has ? cl[0][is - base[0]] : 1.f;
+            const float wv0 = v_has ? cw[1][iv - base[1]] : 0.f, lv0 = v_has ? cl[1][iv - base[1]] : 1.f;
+            const float ols0 = pre[0][is - base[0]], olv0 = pre[1][iv - base[1]];
+            // lane j: decision if the walk has taken j more slashes (iv frozen)
+            int i = is + lane;
+            bool ok = i < n && (i - base[0]) < WALK_WIN;
+            int ii = ok ? i - base[0] : 0;
+            float ds = __fsub_rn(cw[0][ii], olv0);
+            float dv = __fsub_rn(wv0, pre[0][ii]);
+            float cs = __fsub_rn(cl[0][ii], (float)iv); if (cs < 1.0f) cs = 1.0f;
+            float cv = __fsub_rn(lv0, (float)i); if (cv < 1.0f) cv = 1.0f;
+            bool take = !v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
+            bool dead = !(ds > 0.f) && (!v_has || !(dv > 0.f));
+            uint64_t bal = __ballot(ok && take);
+            int run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
+            float gain = ds;
+            int which = 0;
+            if (run == 0) {
+                // the head pick is a vertical; lane j: decision if j more verticals are taken (is frozen)
+                which = 1;
+                i = iv + lane;
+                ok = i < n && (i - base[1]) < WALK_WIN;
+                ii = ok ? i - base[1] : 0;
+                dv = __fsub_rn(cw[1][ii], ols0);
+                ds = __fsub_rn(ws0, pre[1][ii]);
+                cv = __fsub_rn(cl[1][ii], (float)is); if (cv < 1.0f) cv = 1.0f;
+                cs = __fsub_rn(ls0, (float)i); if (cs < 1.0f) cs = 1.0f;
+                take = !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
+                dead = !(dv > 0.f) && (!s_has || !(ds > 0.f));
+                bal = __ballot(ok && take);
+                run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
+                gain = dv;
+            }
+            if (run == 0) { done = true; break; }      // cannot happen (lane 0 repeats the head's test); never spin
+            // picks 0 .. run-1 come from list `which`; stop early when no head has a positive gain
+            const uint64_t deadb = __ballot(dead);
+            int stop_dead = 64;
+            if (early && deadb) stop_dead = __ffsll((unsigned long long)deadb) - 1;
+            int taken = 0;
+            bool exhausted = false;
+            for (int j = 0; j < run; ++j) {
+                if (j == stop_dead) { exhausted = true; break; }
+                sum = __fadd_rn(sum, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gain), j)));
+                ++taken;
+                if (!(sum < target)) break;
+            }
+            head[which] += taken;
+            if (exhausted) { head[0] = n; head[1] = n; done = true; break; }
+        }
     }
-    if (tid == 0) {
-        a.s_cnt[bh] = st.is;
-        a.v_cnt[bh] = st.iv;
-        if (a.accounted) a.accounted[bh] = st.sum;
+    if (lane == 0) {
+        a.s_cnt[bh] = head[0];
+        a.v_cnt[bh] = head[1];
+        if (a.accounted) a.accounted[bh] = sum;
     }
 }
 
