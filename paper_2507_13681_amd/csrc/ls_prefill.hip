@@ -133,11 +133,11 @@ __device__ __forceinline__ void store_out4(float* p, float a, float b, float c, 
 }
 
 // 32 consecutive bits of a bitmap starting at bit `base` (may be negative: those bits read 0).
-__device__ __forceinline__ uint32_t window32(const uint32_t* bits, int64_t base) {
-    if (base <= -32) return 0u;
-    if (base < 0) return bits[0] << (int)(-base);
-    const int wd = (int)(base >> 5), sh = (int)(base & 31);
-    const uint64_t x = (uint64_t)bits[wd] | ((uint64_t)bits[wd + 1] << 32);
+// `bits1` is the bitmap preceded by one zero word (bits1[i + 1] = word i), which makes this branch-free.
+__device__ __forceinline__ uint32_t window32(const uint32_t* bits1, int64_t base) {
+    const int b32 = (int)(base < -32 ? -32 : base) + 32;     // >= 0, bit index in the padded map
+    const int wd = b32 >> 5, sh = b32 & 31;
+    const uint64_t x = (uint64_t)bits1[wd] | ((uint64_t)bits1[wd + 1] << 32);
     return (uint32_t)(x >> sh);
 }
 
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
     unsigned char* k_lds = smem;                                         // [2][K_BYTES]
     unsigned char* vt_lds = smem + 2 * C::K_BYTES;                       // [2][VT_BYTES]
     uint32_t* ob = reinterpret_cast<uint32_t*>(smem + 2 * C::K_BYTES + 2 * C::VT_BYTES);
-    int32_t* colring = reinterpret_cast<int32_t*>(ob + a.words);         // [2][64]
+    int32_t* colring = reinterpret_cast<int32_t*>(ob + a.words + 1);     // [2][64]; ob = zero word + bitmap
     int32_t* wcnt = colring + 128;                                       // [8]
     uint16_t* kbl = reinterpret_cast<uint16_t*>(wcnt + 8);               // [tab_len] active key blocks
     uint8_t* tab = reinterpret_cast<uint8_t*>(kbl + ((a.tab_len + 7) & ~7));
@@ -182,7 +182,8 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
     const T* Qg = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.n_hat * D;
 
     // diagonal bitmap and activity table of this head -> LDS
-    for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i] = a.obits[(int64_t)bh * a.words + i];
+    for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i + 1] = a.obits[(int64_t)bh * a.words + i];
+    if (tid == 0) ob[0] = 0u;
     for (int i = tid; i < a.tab_len; i += PREFILL_THREADS) tab[i] = a.tab[(int64_t)bh * a.tab_len + i];
 
     // this lane's query row and its fragments
@@ -337,14 +338,22 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
             if (base + rv < nv) colv = vi[base + rv];
         }
     };
-    auto fetch = [&](int t) {                              // global -> registers
+    auto fetch = [&](int t) {                              // global -> registers, no divergent branches
         const int64_t gk = src_row(t, rk, colk), gv = src_row(t, rv, colv);
+        const unsigned char* pk = reinterpret_cast<const unsigned char*>(Kg + (gk < 0 ? 0 : gk) * D) + 16 * ck0;
+        const unsigned char* pv = reinterpret_cast<const unsigned char*>(Vg + (gv < 0 ? 0 : gv) * D) + 16 * cv0;
 #pragma unroll
         for (int i = 0; i < C::CPT; ++i) {
+            kreg[i] = *reinterpret_cast<const f32x4*>(pk + 64 * i);
+            vreg[i] = *reinterpret_cast<const f32x4*>(pv + 16 * i);
+        }
+        if (__ballot(gk < 0 || gv < 0) != 0ull) {          // a slot without a row (tail of the context or of the list)
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            kreg[i] = z; vreg[i] = z;
-            if (gk >= 0) kreg[i] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const unsigned char*>(Kg + gk * D) + 16 * (ck0 + 4 * i));
-            if (gv >= 0) vreg[i] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const unsigned char*>(Vg + gv * D) + 16 * (cv0 + i));
+#pragma unroll
+            for (int i = 0; i < C::CPT; ++i) {
+                if (gk < 0) kreg[i] = z;
+                if (gv < 0) vreg[i] = z;
+            }
         }
     };
     auto stash = [&](int t) {                              // registers -> LDS buffer t & 1 (+ column ids)
@@ -406,7 +415,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
                     const int i = __ffsll((unsigned long long)todo) - 1;
                     todo &= todo - 1;
                     const int64_t o = pos - cols[i];       // >= 0 here
-                    if ((ob[o >> 5] >> (o & 31)) & 1u) am &= ~(1ull << i);   // cell already counted on its diagonal
+                    if ((ob[(o >> 5) + 1] >> (o & 31)) & 1u) am &= ~(1ull << i);   // cell already counted on its diagonal
                 }
             }
             am0 = (uint32_t)am; am1 = (uint32_t)(am >> 32);
@@ -442,7 +451,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
 template <typename T, int D>
 static size_t prefill_smem_t(int words, int tab_len) {
     using C = TileCfg<T, D>;
-    return 2 * (size_t)C::K_BYTES + 2 * (size_t)C::VT_BYTES + (size_t)words * 4 + 128 * 4 + 8 * 4 +
+    return 2 * (size_t)C::K_BYTES + 2 * (size_t)C::VT_BYTES + (size_t)(words + 1) * 4 + 128 * 4 + 8 * 4 +
            (size_t)((tab_len + 7) & ~7) * 2 + (size_t)tab_len + 16;
 }
 
