@@ -448,6 +448,338 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 kernel: same tile sequence, masks and softmax as prefill_kernel, but staged the CDNA4 way.
+//   * K and V rows go straight from global memory into LDS (global_load_lds, 16 bytes per lane, no
+//     registers, no LDS store instructions).  A lane's 16 bytes land at LDS base + 16 * lane, so a
+//     tile is laid out as consecutive 16-byte slots: 64 K rows of KS slots (row bytes + one pad
+//     slot) followed by 64 V rows of VS slots (row bytes + four pad slots); the lane that owns a pad
+//     slot simply does not load.
+//   * V stays row-major; the V^T fragments of the P*V product come from the LDS transpose read
+//     ds_read_b64_tr_b16: in a block of 16 lanes, lane s addresses 4 consecutive 16-bit values and
+//     lane L receives value L%4 of the lanes L/4, L/4+4, L/4+8, L/4+12.  With lane s pointing at key
+//     (s/4) and at d-offset 4*(s%4), lane L ends up with four keys of column d = L: two reads give the
+//     eight keys of a fragment.
+// Slots of rows that do not exist (tail of the context or of the column list) are left untouched; both
+// buffers are zeroed once, so such slots only ever hold zeros or older finite rows, and their keys
+// are masked.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+struct DirectCfg {
+    static constexpr int RB = D * 2;                      // bytes per row
+    static constexpr int DS = RB / 16;                    // data slots per row
+    static constexpr int KS = DS + 1;                     // K row: conflict-free 16-byte fragment reads
+    static constexpr int VS = DS + 4;                     // V row: stride = 16 banks mod 64 for the transpose reads
+    static constexpr int K_STRIDE = 16 * KS, V_STRIDE = 16 * VS;
+    static constexpr int K_SLOTS = BN * KS, V_SLOTS = BN * VS, SLOTS = K_SLOTS + V_SLOTS;
+    static constexpr int LOADS = (SLOTS + 63) / 64;       // wave-wide load instructions per tile
+    static constexpr int LPW = (LOADS + 3) / 4;           // ... per wave
+    static constexpr int TILE_BYTES = LOADS * 1024;       // one buffer (rounded up to whole instructions)
+    static constexpr int KSTEPS = D / 16, DBLK = D / 32;
+};
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+template <int D>
+__global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(PrefillArgs a) {
+    using C = DirectCfg<D>;
+    using T = bf16_t;
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* tiles = smem;                                         // [2][TILE_BYTES]
+    uint32_t* ob = reinterpret_cast<uint32_t*>(smem + 2 * C::TILE_BYTES);
+    int32_t* colring = reinterpret_cast<int32_t*>(ob + a.words + 1);     // [3][64]; ob = zero word + bitmap
+    int32_t* wcnt = colring + 192;                                       // [8]
+    uint16_t* kbl = reinterpret_cast<uint16_t*>(wcnt + 8);               // [tab_len] active key blocks | flags << 14
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r32 = lane & 31, g = lane >> 5;
+
+    int bh, qb;
+    {
+        const int id = blockIdx.x;
+        if (a.BH % 8 == 0) {
+            const int x = id & 7, s = id >> 3;
+            bh = x + 8 * (s / a.nqb);
+            qb = a.nqb - 1 - (s % a.nqb);
+        } else {
+            bh = id / a.nqb;
+            qb = a.nqb - 1 - (id % a.nqb);
+        }
+    }
+    const int b = bh / a.Hq, h = bh % a.Hq, kvh = h / a.G;
+    const int64_t n = a.n, row0 = n - a.n_hat;
+    const int64_t blockpos = a.pos0 + (int64_t)qb * BM;                  // multiple of 128
+    const int64_t posmax = (blockpos + BM - 1 < n - 1) ? blockpos + BM - 1 : n - 1;
+    const unsigned char* Kg = reinterpret_cast<const unsigned char*>(a.k) + ((int64_t)b * a.Hkv + kvh) * n * C::RB;
+    const unsigned char* Vg = reinterpret_cast<const unsigned char*>(a.v) + ((int64_t)b * a.Hkv + kvh) * n * C::RB;
+    const T* Qg = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.n_hat * D;
+    const uint8_t* tabg = a.tab + (int64_t)bh * a.tab_len;
+
+    for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i + 1] = a.obits[(int64_t)bh * a.words + i];
+    if (tid == 0) ob[0] = 0u;
+    {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        for (int i = tid; i < 2 * C::TILE_BYTES / 16; i += PREFILL_THREADS) reinterpret_cast<f32x4*>(tiles)[i] = z;
+    }
+
+    const int64_t pos = blockpos + 32 * wv + r32;
+    const bool row_ok = (pos >= row0) && (pos < n);
+    Frag<T> qf[C::KSTEPS];
+    if (row_ok) {
+        const T* qrow = Qg + (pos - row0) * D;
+#pragma unroll
+        for (int c = 0; c < C::KSTEPS; ++c) load_frag(qf[c], qrow + 16 * c + 8 * g);
+    } else {
+#pragma unroll
+        for (int c = 0; c < C::KSTEPS; ++c) zero_frag(qf[c]);
+    }
+    const bool all_ok = __ballot(row_ok) == ~0ull;
+
+    // ---- ordered list of the key blocks phase 1 visits (flags of the per-j table ride in bits 14-15)
+    const int64_t jb = blockpos / BN;                      // even
+    const int kb_hi = (int)(posmax / BN);
+    int n1 = 0;
+    for (int base = 0; base <= kb_hi; base += PREFILL_THREADS) {
+        const int kb = base + tid;
+        const uint8_t f = kb <= kb_hi ? tabg[jb - kb + 1] : (uint8_t)0;
+        const bool act = f & 1;
+        const uint64_t bal = __ballot(act);
+        if (lane == 0) wcnt[wv] = __popcll(bal);
+        __syncthreads();
+        int off = n1;
+        for (int w2 = 0; w2 < wv; ++w2) off += wcnt[w2];
+        if (act) kbl[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)(kb | ((f & 2) << 13));
+        n1 += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        __syncthreads();
+    }
+    int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
+    const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
+    if (a.hflag[bh] & 1) nv = 0;                           // every diagonal is selected: phase 1 covers all cells
+    if (nv > 0 && (int64_t)vi[nv - 1] > posmax) {          // ascending list: binary search for the first column > posmax
+        int lo = 0, hi = nv - 1;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if ((int64_t)vi[mid] > posmax) hi = mid; else lo = mid + 1; }
+        nv = lo;
+    }
+    const int n2 = (nv + BN - 1) / BN;
+    const int ntiles = n1 + n2;
+
+    f32x16 oacc[C::DBLK];
+#pragma unroll
+    for (int i = 0; i < C::DBLK; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;                  // m_run in raw logit units
+    const float sc2 = a.scale_log2e;
+
+    // per-lane constant part of the transpose-read address (see the header comment)
+    const int L16 = lane & 15, beta = (lane >> 4) & 1;
+    const int vlane_off = (4 * g + (L16 >> 2)) * C::V_STRIDE + (16 * beta + 4 * (L16 & 3)) * 2;
+
+    auto process = [&](const unsigned char* tile, uint32_t am0, uint32_t am1, bool full) {
+        const unsigned char* kt = tile;
+        const unsigned char* vt = tile + C::K_SLOTS * 16;
+        f32x16 s[2];
+        bool act[2];
+        act[0] = __ballot(am0 != 0u) != 0ull;
+        act[1] = __ballot(am1 != 0u) != 0ull;
+        if (!act[0] && !act[1]) return;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+            if (act[sub]) {
+                const unsigned char* krow = kt + (32 * sub + r32) * C::K_STRIDE + 16 * g;
+#pragma unroll
+                for (int c = 0; c < C::KSTEPS; ++c) {
+                    Frag<T> kf;
+                    load_frag(kf, krow + 32 * c);
+                    mma(s[sub], kf, qf[c]);        // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
+                }
+            }
+        }
+        float mx = -INFINITY;
+        if (full) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const uint32_t am = sub ? am1 : am0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kbit = 8 * (r >> 2) + 4 * g + (r & 3);
+                    const float x = ((am >> kbit) & 1u) ? s[sub][r] : -INFINITY;
+                    s[sub][r] = x;
+                    mx = fmaxf(mx, x);
+                }
+            }
+        }
+        mx = fmaxf(mx, xor32(mx));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = fast_exp2((m_run - m_safe) * sc2);
+        const float mneg = -m_safe * sc2;
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(__builtin_fmaf(s[sub][r], sc2, mneg));
+                s[sub][r] = p;
+                psum += p;
+            }
+        l_run = l_run * corr + psum;
+        if (__ballot(corr != 1.0f) != 0ull) {
+#pragma unroll
+            for (int i = 0; i < C::DBLK; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+        }
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {                  // 16-key chunk q4: keys 16*q4 .. 16*q4+15 of the tile
+            if (!act[q4 >> 1]) continue;
+            float pv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pv[e] = s[q4 >> 1][8 * (q4 & 1) + e];
+            Frag<T> pf;
+            pack_frag(pf, pv);
+#pragma unroll
+            for (int i = 0; i < C::DBLK; ++i) {
+                const unsigned char* va = vt + vlane_off + 16 * q4 * C::V_STRIDE + 64 * i;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::V_STRIDE));
+                struct U { s16x4 a, b; } u = {lo, hi};
+                Frag<T> vf;
+                vf.v = __builtin_bit_cast(bf16x8, u);
+                mma(oacc[i], vf, pf);              // O^T[d][row] += V^T[d][key] P^T[key][row]
+            }
+        }
+    };
+
+    // ---- staging: wave wv issues load instructions q = wv + 4*i; instruction q fills slots 64q .. 64q+63
+    int sdesc[C::LPW];                                     // slot -> row | chunk << 8 | is_v << 16 | live << 17
+#pragma unroll
+    for (int i = 0; i < C::LPW; ++i) {
+        const int slot = (wv + 4 * i) * 64 + lane;
+        int d = 0;
+        if (slot < C::K_SLOTS) { const int row = slot / C::KS, c = slot % C::KS; d = row | (c << 8) | ((c < C::DS) << 17); }
+        else if (slot < C::SLOTS) { const int s2 = slot - C::K_SLOTS, row = s2 / C::VS, c = s2 % C::VS; d = row | (c << 8) | (1 << 16) | ((c < C::DS) << 17); }
+        sdesc[i] = d;
+    }
+    auto issue = [&](int t) {                              // global -> LDS buffer t & 1 for tile t
+        unsigned char* dst = tiles + (t & 1) * C::TILE_BYTES;
+        const bool contiguous = t < n1;
+        const int64_t key0 = contiguous ? (int64_t)(kbl[t] & 0x3FFF) * BN : 0;
+        const int32_t* cols = colring + (t % 3) * BN;
+#pragma unroll
+        for (int i = 0; i < C::LPW; ++i) {
+            const int d = sdesc[i], row = d & 0xFF, c = (d >> 8) & 0xFF;
+            int64_t grow = contiguous ? key0 + row : (int64_t)cols[row];
+            const bool live = ((d >> 17) & 1) && grow >= 0 && grow < n;
+            if (live) {
+                const unsigned char* src = (((d >> 16) & 1) ? Vg : Kg) + grow * C::RB + 16 * c;
+                __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                                 (void __attribute__((address_space(3)))*)(dst + (wv + 4 * i) * 1024), 16, 0, 0);
+            }
+        }
+    };
+    auto put_cols = [&](int t) {                           // column ids of gathered tile t -> LDS (read when t is issued / masked)
+        if (t >= n1 && t < ntiles && tid < BN) {
+            const int idx = (t - n1) * BN + tid;
+            colring[(t % 3) * BN + tid] = idx < nv ? vi[idx] : -1;
+        }
+    };
+
+    __syncthreads();                                       // zeroed buffers, bitmap, kbl visible
+    put_cols(0);
+    put_cols(1);
+    __syncthreads();
+    if (ntiles > 0) issue(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) issue(t + 1);
+        put_cols(t + 2);
+        uint32_t am0 = 0u, am1 = 0u;
+        bool full = false;
+        if (t < n1) {
+            const int e = kbl[t];
+            const int64_t key0 = (int64_t)(e & 0x3FFF) * BN;
+            const bool fullflag = (e >> 14) & 1;
+            if (!row_ok) { am0 = am1 = 0u; }
+            else if (fullflag) { am0 = am1 = 0xFFFFFFFFu; }
+            else {
+                const int64_t d0 = pos - key0;             // diagonal of the tile's first key
+                am0 = __brev(window32(ob, d0 - 31));
+                am1 = __brev(window32(ob, d0 - 63));
+            }
+            full = fullflag && all_ok;
+        } else {
+            const int32_t* cols = colring + (t % 3) * BN;
+            const int base = (t - n1) * BN;
+            const int cnt = nv - base < BN ? nv - base : BN;
+            const int32_t mycol = lane < cnt ? cols[lane] : 0;
+            const uint8_t f = lane < cnt ? tabg[jb - (mycol >> 6) + 1] : (uint8_t)3;
+            const uint64_t drop = __ballot(f == 3);        // wholly covered by phase 1 (or no such slot)
+            const uint64_t chk = __ballot(f == 1);         // partly covered: test cell by cell
+            uint64_t am = 0ull;
+            if (row_ok) {
+                if ((int64_t)cols[cnt - 1] <= pos) am = cnt >= 64 ? ~0ull : ((1ull << cnt) - 1ull);
+                else for (int i = 0; i < cnt; ++i) if ((int64_t)cols[i] <= pos) am |= 1ull << i;
+                am &= ~drop;
+                uint64_t todo = chk & am;
+                while (todo) {
+                    const int i = __ffsll((unsigned long long)todo) - 1;
+                    todo &= todo - 1;
+                    const int64_t o = pos - cols[i];       // >= 0 here
+                    if ((ob[(o >> 5) + 1] >> (o & 31)) & 1u) am &= ~(1ull << i);   // cell already counted on its diagonal
+                }
+            }
+            am0 = (uint32_t)am; am1 = (uint32_t)(am >> 32);
+        }
+        process(tiles + (t & 1) * C::TILE_BYTES, am0, am1, full);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                // this wave's loads of tile t+1 have landed
+        __syncthreads();
+    }
+
+    const float l_tot = l_run + xor32(l_run);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    if (row_ok) {
+        T* orow = reinterpret_cast<T*>(a.out) + ((int64_t)bh * a.n_hat + (pos - row0)) * D;
+#pragma unroll
+        for (int i = 0; i < C::DBLK; ++i)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int d0 = 32 * i + 8 * rq + 4 * g;
+                store_out4(orow + d0, oacc[i][4 * rq] * inv, oacc[i][4 * rq + 1] * inv,
+                           oacc[i][4 * rq + 2] * inv, oacc[i][4 * rq + 3] * inv);
+            }
+        if (a.lse && g == 0)
+            a.lse[(int64_t)bh * a.n_hat + (pos - row0)] =
+                l_tot > 0.f ? (m_run * sc2 + log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
+    }
+}
+
+template <int D>
+static size_t prefill_bf16_smem(int words, int tab_len) {
+    return 2 * (size_t)DirectCfg<D>::TILE_BYTES + (size_t)(words + 1) * 4 + 192 * 4 + 8 * 4 +
+           (size_t)((tab_len + 7) & ~7) * 2 + 16;
+}
+
+template <int D>
+static hipError_t launch_prefill_bf16(const PrefillArgs& a, hipStream_t st) {
+    const size_t smem = prefill_bf16_smem<D>(a.words, a.tab_len);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_bf16_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_bf16_kernel<D>), dim3(a.BH * a.nqb), dim3(PREFILL_THREADS), smem, st, a);
+    return hipGetLastError();
+}
+
 template <typename T, int D>
 static size_t prefill_smem_t(int words, int tab_len) {
     using C = TileCfg<T, D>;
@@ -466,8 +798,8 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
 }
 
 size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len) {
-    if (dtype == 0 && d == 128) return prefill_smem_t<bf16_t, 128>(words, tab_len);
-    if (dtype == 0 && d == 64) return prefill_smem_t<bf16_t, 64>(words, tab_len);
+    if (dtype == 0 && d == 128) return prefill_bf16_smem<128>(words, tab_len);
+    if (dtype == 0 && d == 64) return prefill_bf16_smem<64>(words, tab_len);
     if (dtype == 1 && d == 128) return prefill_smem_t<float, 128>(words, tab_len);
     return prefill_smem_t<float, 64>(words, tab_len);
 }
@@ -482,8 +814,8 @@ hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st) {
 }
 
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st) {
-    if (dtype == 0 && d == 128) return launch_prefill_t<bf16_t, 128>(a, st);
-    if (dtype == 0 && d == 64) return launch_prefill_t<bf16_t, 64>(a, st);
+    if (dtype == 0 && d == 128) return launch_prefill_bf16<128>(a, st);
+    if (dtype == 0 && d == 64) return launch_prefill_bf16<64>(a, st);
     if (dtype == 1 && d == 128) return launch_prefill_t<float, 128>(a, st);
     if (dtype == 1 && d == 64) return launch_prefill_t<float, 64>(a, st);
     return hipErrorInvalidValue;
