@@ -26,6 +26,9 @@
 
 namespace ls {
 
+#ifndef LS_RING_S
+#define LS_RING_S 4       // K fragments in flight ahead of the QK^T products (0: leave the order to the compiler)
+#endif
 constexpr int BM = 128;   // query rows per workgroup
 constexpr int BN = 64;    // keys per tile
 constexpr int PREFILL_THREADS = 256;
@@ -460,9 +463,8 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
 //     lane L receives value L%4 of the lanes L/4, L/4+4, L/4+8, L/4+12.  With lane s pointing at key
 //     (s/4) and at d-offset 4*(s%4), lane L ends up with four keys of column d = L: two reads give the
 //     eight keys of a fragment.
-// Slots of rows that do not exist (tail of the context or of the column list) are left untouched; both
-// buffers are zeroed once, so such slots only ever hold zeros or older finite rows, and their keys
-// are masked.
+// Slots of rows that do not exist (tail of the context or of the column list) re-load an existing row;
+// their keys are masked, so only finiteness of the staged values matters.
 // ---------------------------------------------------------------------------------------------
 template <int D>
 struct DirectCfg {
@@ -517,11 +519,6 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
 
     for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i + 1] = a.obits[(int64_t)bh * a.words + i];
     if (tid == 0) ob[0] = 0u;
-    {
-        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        for (int i = tid; i < 2 * C::TILE_BYTES / 16; i += PREFILL_THREADS) reinterpret_cast<f32x4*>(tiles)[i] = z;
-    }
-
     const int64_t pos = blockpos + 32 * wv + r32;
     const bool row_ok = (pos >= row0) && (pos < n);
     Frag<T> qf[C::KSTEPS];
@@ -583,17 +580,36 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
         act[0] = __ballot(am0 != 0u) != 0ull;
         act[1] = __ballot(am1 != 0u) != 0ull;
         if (!act[0] && !act[1]) return;
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[0] = zero16; s[1] = zero16;
+        if (act[0] && act[1]) {
+            // 2 * KSTEPS products; K fragments are fetched RING_S steps ahead of their use
+            constexpr int NP = 2 * C::KSTEPS;
+            const unsigned char* kbase = kt + r32 * C::K_STRIDE + 16 * g;
+            Frag<T> kf[NP];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+            for (int i = 0; i < NP; ++i) load_frag(kf[i], kbase + (i & 1) * 32 * C::K_STRIDE + 32 * (i >> 1));
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
-            if (act[sub]) {
+            for (int i = 0; i < NP; ++i) mma(s[i & 1], kf[i], qf[i >> 1]);   // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
+#if LS_RING_S > 0
+            __builtin_amdgcn_sched_group_barrier(0x100, LS_RING_S, 0);
+#pragma unroll
+            for (int i = 0; i < NP - LS_RING_S; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, LS_RING_S, 0);
+#endif
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                if (!act[sub]) continue;
                 const unsigned char* krow = kt + (32 * sub + r32) * C::K_STRIDE + 16 * g;
 #pragma unroll
                 for (int c = 0; c < C::KSTEPS; ++c) {
                     Frag<T> kf;
                     load_frag(kf, krow + 32 * c);
-                    mma(s[sub], kf, qf[c]);        // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
+                    mma(s[sub], kf, qf[c]);
                 }
             }
         }
@@ -659,30 +675,62 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
         }
     };
 
-    // ---- staging: wave wv issues load instructions q = wv + 4*i; instruction q fills slots 64q .. 64q+63
-    int sdesc[C::LPW];                                     // slot -> row | chunk << 8 | is_v << 16 | live << 17
+    // ---- staging: wave wv issues load instructions q = wv + 4*i; instruction q fills slots 64q .. 64q+63.
+    // Instructions 0 .. K_LOADS-1 carry K rows, the rest V rows (both slot counts are multiples of 64).
+    // A pad slot re-loads chunk 0 of its row, a row beyond the context re-loads the last row, a missing
+    // column re-loads row 0: every slot is always written with finite data and needs no exec masking.
+    constexpr int K_LOADS = C::K_SLOTS / 64;
+    static_assert(C::K_SLOTS % 64 == 0 && C::V_SLOTS % 64 == 0, "slot counts must be whole instructions");
+    int srow[C::LPW];                                      // tile row of this lane's slot in instruction i
+    uint32_t soff[C::LPW];                                 // row * RB + 16 * chunk
 #pragma unroll
     for (int i = 0; i < C::LPW; ++i) {
-        const int slot = (wv + 4 * i) * 64 + lane;
-        int d = 0;
-        if (slot < C::K_SLOTS) { const int row = slot / C::KS, c = slot % C::KS; d = row | (c << 8) | ((c < C::DS) << 17); }
-        else if (slot < C::SLOTS) { const int s2 = slot - C::K_SLOTS, row = s2 / C::VS, c = s2 % C::VS; d = row | (c << 8) | (1 << 16) | ((c < C::DS) << 17); }
-        sdesc[i] = d;
+        const int q = wv + 4 * i;
+        const int slot = q * 64 + lane;
+        int row, c;
+        if (q < K_LOADS) { row = slot / C::KS; c = slot % C::KS; }
+        else { const int s2 = slot - C::K_SLOTS; row = s2 / C::VS; c = s2 % C::VS; }
+        if (c >= C::DS) c = 0;
+        if (row > BN - 1) row = BN - 1;                    // instructions past the tile are never issued
+        srow[i] = row;
+        soff[i] = (uint32_t)(row * C::RB + 16 * c);
     }
     auto issue = [&](int t) {                              // global -> LDS buffer t & 1 for tile t
         unsigned char* dst = tiles + (t & 1) * C::TILE_BYTES;
-        const bool contiguous = t < n1;
-        const int64_t key0 = contiguous ? (int64_t)(kbl[t] & 0x3FFF) * BN : 0;
-        const int32_t* cols = colring + (t % 3) * BN;
+        if (t < n1) {
+            const int64_t key0 = (int64_t)(kbl[t] & 0x3FFF) * BN;
+            const unsigned char* kb_ = Kg + key0 * C::RB;
+            const unsigned char* vb_ = Vg + key0 * C::RB;
+            if (key0 + BN <= n) {
 #pragma unroll
-        for (int i = 0; i < C::LPW; ++i) {
-            const int d = sdesc[i], row = d & 0xFF, c = (d >> 8) & 0xFF;
-            int64_t grow = contiguous ? key0 + row : (int64_t)cols[row];
-            const bool live = ((d >> 17) & 1) && grow >= 0 && grow < n;
-            if (live) {
-                const unsigned char* src = (((d >> 16) & 1) ? Vg : Kg) + grow * C::RB + 16 * c;
-                __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                                 (void __attribute__((address_space(3)))*)(dst + (wv + 4 * i) * 1024), 16, 0, 0);
+                for (int i = 0; i < C::LPW; ++i) {
+                    const int q = wv + 4 * i;
+                    if (q < C::LOADS)
+                        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)((q < K_LOADS ? kb_ : vb_) + soff[i]),
+                                                         (void __attribute__((address_space(3)))*)(dst + q * 1024), 16, 0, 0);
+                }
+            } else {                                       // last key block of the context: clamp the rows
+                const int last = (int)(n - 1 - key0);
+#pragma unroll
+                for (int i = 0; i < C::LPW; ++i) {
+                    const int q = wv + 4 * i;
+                    const uint32_t off = srow[i] <= last ? soff[i] : soff[i] - (uint32_t)((srow[i] - last) * C::RB);
+                    if (q < C::LOADS)
+                        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)((q < K_LOADS ? kb_ : vb_) + off),
+                                                         (void __attribute__((address_space(3)))*)(dst + q * 1024), 16, 0, 0);
+                }
+            }
+        } else {
+            const int32_t* cols = colring + (t % 3) * BN;
+#pragma unroll
+            for (int i = 0; i < C::LPW; ++i) {
+                const int q = wv + 4 * i;
+                int32_t col = cols[srow[i]];
+                if (col < 0) col = 0;
+                const uint32_t off = (uint32_t)col * C::RB + (soff[i] - (uint32_t)(srow[i] * C::RB));
+                if (q < C::LOADS)
+                    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)((q < K_LOADS ? Kg : Vg) + off),
+                                                     (void __attribute__((address_space(3)))*)(dst + q * 1024), 16, 0, 0);
             }
         }
     };
