@@ -638,39 +638,44 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
         const float corr = fast_exp2((m_run - m_safe) * sc2);
         const float mneg = -m_safe * sc2;
         m_run = m_new;
-        float psum = 0.f;
+        float ps4[4] = {0.f, 0.f, 0.f, 0.f};               // four short add chains instead of one long one
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float p = fast_exp2(__builtin_fmaf(s[sub][r], sc2, mneg));
                 s[sub][r] = p;
-                psum += p;
+                ps4[r & 3] += p;
             }
-        l_run = l_run * corr + psum;
+        l_run = l_run * corr + ((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
         if (__ballot(corr != 1.0f) != 0ull) {
 #pragma unroll
             for (int i = 0; i < C::DBLK; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
         }
+        auto vt_frag = [&](Frag<T>& vf, int q4, int i) {     // V^T fragment: keys 16*q4.., output block i
+            const unsigned char* va = vt + vlane_off + 16 * q4 * C::V_STRIDE + 64 * i;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::V_STRIDE));
+            struct U { s16x4 a, b; } u = {lo, hi};
+            vf.v = __builtin_bit_cast(bf16x8, u);
+        };
+        {
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {                  // 16-key chunk q4: keys 16*q4 .. 16*q4+15 of the tile
-            if (!act[q4 >> 1]) continue;
-            float pv[8];
+            for (int q4 = 0; q4 < 4; ++q4) {              // 16-key chunk q4: keys 16*q4 .. 16*q4+15 of the tile
+                if (!act[q4 >> 1]) continue;
+                float pv[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pv[e] = s[q4 >> 1][8 * (q4 & 1) + e];
-            Frag<T> pf;
-            pack_frag(pf, pv);
+                for (int e = 0; e < 8; ++e) pv[e] = s[q4 >> 1][8 * (q4 & 1) + e];
+                Frag<T> pf;
+                pack_frag(pf, pv);
 #pragma unroll
-            for (int i = 0; i < C::DBLK; ++i) {
-                const unsigned char* va = vt + vlane_off + 16 * q4 * C::V_STRIDE + 64 * i;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::V_STRIDE));
-                struct U { s16x4 a, b; } u = {lo, hi};
-                Frag<T> vf;
-                vf.v = __builtin_bit_cast(bf16x8, u);
-                mma(oacc[i], vf, pf);              // O^T[d][row] += V^T[d][key] P^T[key][row]
+                for (int i = 0; i < C::DBLK; ++i) {
+                    Frag<T> vf;
+                    vt_frag(vf, q4, i);
+                    mma(oacc[i], vf, pf);
+                }
             }
         }
     };
