@@ -143,7 +143,7 @@ def main():
                   "mixed": int(((ns > 0) & (nv > 0) & ~((nv >= cfg.n) & (ns >= cfg.n))).sum())},
         "ms_per_call": {a: round(b, 4) for a, b in br.items()},
         "wall_s": round(wall, 3),
-        "roofline": {"kernel": "prefill_kernel", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
+        "roofline": {"kernel": "prefill_bf16_kernel" if cfg.dtype == "bf16" else "prefill_kernel", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes,
                      "kernel_ms": round(kern_ms, 4), "launches": launches},
         "paper_context": "no speed-up printed in the paper's text; its machine: 1x H100 80GB + 8-core Xeon Gold 6542Y",

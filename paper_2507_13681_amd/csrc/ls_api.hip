@@ -85,7 +85,9 @@ inline int words_of(int64_t n) { return (int)((n + 31) / 32) + 8; }
 inline int tab_len_of(int64_t n) { return (int)(n / 64) + 4; }
 size_t ws_prefill(const ls_shape* s) {
     const size_t BH = (size_t)s->B * s->Hq;
-    return up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH);
+    const size_t items = BH * (size_t)(s->n / 128 + 2);          // (head, row block) work items, upper bound
+    return up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH) + up(BH * 4) +
+           up(8 * items * 4) + 2 * up(8 * 4);
 }
 size_t ws_compress(const ls_shape* s) {
     return ws_score(s, false) + up((size_t)s->B * s->Hkv * (size_t)s->n * 4);
@@ -205,19 +207,33 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     Bump bp{c->ws, c->ws_bytes, 0};
     uint32_t* obits = bp.take<uint32_t>((size_t)BH * words);
     uint8_t* hflag = bp.take<uint8_t>((size_t)BH);
+    uint32_t* cost = bp.take<uint32_t>((size_t)BH);
+    const int bm = ls::prefill_block_rows();
+    const int64_t pos0 = (s->n - s->n_hat) / bm * bm;
+    const int nqb = (int)((s->n - pos0 + bm - 1) / bm);
+    if (nqb > 65535) return fail(c, LS_ESHAPE, "ls_sparse_prefill: too many row blocks");
+    uint32_t* queue = bp.take<uint32_t>(8 * (size_t)BH * nqb);
+    int32_t* qlen = bp.take<int32_t>(8);
+    int32_t* qhead = bp.take<int32_t>(8);
     uint8_t* tab = bp.take<uint8_t>((size_t)BH * tab_len);
     if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_sparse_prefill: workspace of %zu bytes is too small", c->ws_bytes);
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: hipSetDevice failed");
     ls::PlanArgs p{};
     p.n = s->n; p.words = words; p.tab_len = tab_len; p.v_idx = v_idx; p.v_cnt = v_cnt; p.s_idx = s_idx; p.s_cnt = s_cnt;
-    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.tab = tab; p.hflag = hflag;
+    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.tab = tab; p.hflag = hflag; p.cost = cost;
     hipError_t e = ls::launch_plan(p, BH, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(plan): %s", hipGetErrorString(e));
+    ls::SchedArgs sa{};
+    sa.BH = BH; sa.G = s->Hq / s->Hkv; sa.Hq = s->Hq; sa.Hkv = s->Hkv; sa.nqb = nqb; sa.cost = cost;
+    sa.queue = queue; sa.qlen = qlen; sa.qhead = qhead;
+    e = ls::launch_sched(sa, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(sched): %s", hipGetErrorString(e));
     ls::PrefillArgs a{};
     a.q = q; a.k = k; a.v = v; a.out = out; a.lse = lse; a.n = s->n; a.n_hat = s->n_hat;
-    a.pos0 = (s->n - s->n_hat) / 128 * 128;
+    a.queue = queue; a.qlen = qlen; a.qhead = qhead; a.qcap = BH * nqb;
+    a.pos0 = pos0;
     a.Hq = s->Hq; a.Hkv = s->Hkv; a.G = s->Hq / s->Hkv; a.BH = BH;
-    a.nqb = (int)((s->n - a.pos0 + 127) / 128);
+    a.nqb = nqb;
     a.words = words; a.tab_len = tab_len; a.scale_log2e = scale_log2e(s);
     a.obits = obits; a.tab = tab; a.hflag = hflag; a.v_idx = v_idx; a.v_cnt = v_cnt; a.cap_v = cap_v;
     hipEvent_t e0 = nullptr, e1 = nullptr;

@@ -48,6 +48,16 @@ struct PlanArgs {
     uint32_t* obits;          // [BH][words]
     uint8_t* tab;             // [BH][tab_len]
     uint8_t* hflag;           // [BH]
+    uint32_t* cost;           // [BH] estimated tiles per row block (for the work queues)
+};
+
+// Work queues of the sparse attention kernel: one list of (head, row block) items per XCD.
+struct SchedArgs {
+    int BH, G, Hq, Hkv, nqb;
+    const uint32_t* cost;     // [BH]
+    uint32_t* queue;          // [8][BH * nqb] items: bh << 16 | qb
+    int32_t* qlen;            // [8]
+    int32_t* qhead;           // [8] next item to hand out
 };
 
 struct PrefillArgs {
@@ -61,6 +71,10 @@ struct PrefillArgs {
     const uint8_t *tab, *hflag;
     const int32_t *v_idx, *v_cnt;
     int cap_v;
+    const uint32_t* queue;    // work queues built by sched_kernel
+    const int32_t* qlen;
+    int32_t* qhead;
+    int qcap;                 // entries per queue
 };
 
 hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st);
@@ -70,7 +84,9 @@ hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st);
 hipError_t run_gather_rows(const void* src, void* dst, const int32_t* keep_idx, const int32_t* keep_cnt,
                            int BK, int64_t len, int budget, int row_bytes, hipStream_t st);
 hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st);
+hipError_t launch_sched(const SchedArgs& a, hipStream_t st);
 hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st);
 size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len);
+int prefill_block_rows();
 
 }  // namespace ls

@@ -84,6 +84,106 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     }
     __syncthreads();
     if (tid == 0) a.hflag[bh] = (total_bits == (int)n) ? 1 : 0;
+    // cost estimate: table entries with a selected diagonal (key blocks a late row block visits) plus
+    // packed column tiles
+    __shared__ int active_entries;
+    if (tid == 0) active_entries = 0;
+    __syncthreads();
+    int act = 0;
+    for (int e = tid; e < a.tab_len; e += blockDim.x) act += a.tab[(int64_t)bh * a.tab_len + e] & 1;
+    atomicAdd(&active_entries, act);
+    __syncthreads();
+    if (tid == 0) {
+        int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
+        if (total_bits == (int)n) nv = 0;
+        a.cost[bh] = (uint32_t)(active_entries + (nv + 63) / 64 + 1);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// sched: builds the 8 work queues.  The query heads of one KV head stay together (they share K/V
+// tiles in one L2); KV groups are dealt to the XCDs heaviest first, each to the XCD with the least
+// work so far.  Inside a queue later row blocks come first and the G heads of a group are adjacent.
+// One workgroup; groups beyond SCHED_MAX_GROUPS fall back to round-robin dealing.
+// ---------------------------------------------------------------------------------------------
+constexpr int SCHED_MAX_GROUPS = 2048;
+__global__ __launch_bounds__(256) void sched_kernel(SchedArgs a) {
+    __shared__ uint32_t gcost[SCHED_MAX_GROUPS];
+    __shared__ uint16_t order[SCHED_MAX_GROUPS];          // groups by decreasing cost
+    __shared__ uint16_t bin_of[SCHED_MAX_GROUPS], slot_of[SCHED_MAX_GROUPS];
+    __shared__ int bin_groups[8];
+    const int tid = threadIdx.x;
+    const int groups = a.BH / a.G;
+    const bool sorted = groups <= SCHED_MAX_GROUPS;
+    if (sorted) {
+        for (int gi = tid; gi < groups; gi += 256) {
+            const int b = gi / a.Hkv, kvh = gi % a.Hkv;
+            uint32_t c = 0;
+            for (int g = 0; g < a.G; ++g) c += a.cost[b * a.Hq + kvh * a.G + g];
+            gcost[gi] = c;
+        }
+        __syncthreads();
+        for (int gi = tid; gi < groups; gi += 256) {       // rank sort (ties: smaller index first)
+            const uint32_t c = gcost[gi];
+            int rank = 0;
+            for (int o = 0; o < groups; ++o) { const uint32_t d = gcost[o]; rank += (d > c) || (d == c && o < gi); }
+            order[rank] = (uint16_t)gi;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint64_t load[8]; int cnt[8];
+            for (int x = 0; x < 8; ++x) { load[x] = 0; cnt[x] = 0; }
+            for (int r = 0; r < groups; ++r) {
+                const int gi = order[r];
+                int best = 0;
+                for (int x = 1; x < 8; ++x) if (load[x] < load[best]) best = x;
+                bin_of[gi] = (uint16_t)best; slot_of[gi] = (uint16_t)cnt[best];
+                load[best] += gcost[gi] + 1; ++cnt[best];
+            }
+            for (int x = 0; x < 8; ++x) bin_groups[x] = cnt[x];
+        }
+        __syncthreads();
+    }
+    const int per_bin_rr = (groups + 7) / 8;
+    // item (gi, g, qb) -> queue bin, position (nqb-1-qb) * (groups in bin * G) + slot * G + g
+    const int64_t total = (int64_t)a.BH * a.nqb;
+    const int64_t qcap = total;
+    for (int64_t it = tid; it < total; it += 256) {
+        const int bh = (int)(it / a.nqb), qb = (int)(it % a.nqb);
+        const int b = bh / a.Hq, h = bh % a.Hq, gi = b * a.Hkv + h / a.G, g = h % a.G;
+        int bin, slot, ng;
+        if (sorted) { bin = bin_of[gi]; slot = slot_of[gi]; ng = bin_groups[bin]; }
+        else { bin = gi & 7; slot = gi >> 3; ng = (groups - bin + 7) / 8; }
+        (void)per_bin_rr;
+        const int64_t posn = (int64_t)(a.nqb - 1 - qb) * ng * a.G + (int64_t)slot * a.G + g;
+        a.queue[(int64_t)bin * qcap + posn] = ((uint32_t)bh << 16) | (uint32_t)qb;
+    }
+    if (tid < 8) {
+        const int ng = sorted ? bin_groups[tid] : (groups - tid + 7) / 8;
+        a.qlen[tid] = ng * a.G * a.nqb;
+        a.qhead[tid] = 0;
+    }
+}
+
+// Persistent launch: enough workgroups to fill the chip at any occupancy this kernel reaches
+// (256 CUs x up to 4 resident workgroups); surplus workgroups find the queues empty and leave.
+static int persistent_grid(const PrefillArgs& a) {
+    const int64_t total = (int64_t)a.BH * a.nqb;
+    return (int)(total < 1024 ? total : 1024);
+}
+
+// Next work item for this workgroup: its own XCD's queue first, then the others in ring order.
+// Returns -1 when every queue is drained (each queue hands out each item once; the scan is finite).
+__device__ __forceinline__ int pop_item(const PrefillArgs& a, int my_x) {
+    for (int k = 0; k < 8; ++k) {
+        const int x = (my_x + k) & 7;
+        const int len = a.qlen[x];
+        if (__atomic_load_n(&a.qhead[x], __ATOMIC_RELAXED) < len) {
+            const int i = atomicAdd(&a.qhead[x], 1);
+            if (i < len) return (int)a.queue[(int64_t)x * a.qcap + i];
+        }
+    }
+    return -1;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -162,20 +262,14 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r32 = lane & 31, g = lane >> 5;
 
-    // workgroup -> (head, row block); heads are spread over the 8 XCDs so that all row blocks of a
-    // head run on one XCD and share its L2 for the head's K/V rows.
-    int bh, qb;
-    {
-        const int id = blockIdx.x;
-        if (a.BH % 8 == 0) {
-            const int x = id & 7, s = id >> 3;
-            bh = x + 8 * (s / a.nqb);
-            qb = a.nqb - 1 - (s % a.nqb);
-        } else {
-            bh = id / a.nqb;
-            qb = a.nqb - 1 - (id % a.nqb);
-        }
-    }
+    __shared__ int item_s;
+  for (;;) {                                               // persistent: one (head, row block) item per trip
+    __syncthreads();                                       // everyone is done with the previous item's LDS
+    if (tid == 0) item_s = pop_item(a, blockIdx.x & 7);    // taken only when needed: items are coarse, reserving early hurts the tail
+    __syncthreads();
+    const int item = item_s;
+    if (item < 0) break;
+    const int bh = item >> 16, qb = item & 0xFFFF;
     const int b = bh / a.Hq, h = bh % a.Hq, kvh = h / a.G;
     const int64_t n = a.n, row0 = n - a.n_hat;
     const int64_t blockpos = a.pos0 + (int64_t)qb * BM;                  // multiple of 128
@@ -449,6 +543,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
             a.lse[(int64_t)bh * a.n_hat + (pos - row0)] =
                 l_tot > 0.f ? (m_run * sc2 + log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
     }
+  }                                                        // next item
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -496,18 +591,14 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r32 = lane & 31, g = lane >> 5;
 
-    int bh, qb;
-    {
-        const int id = blockIdx.x;
-        if (a.BH % 8 == 0) {
-            const int x = id & 7, s = id >> 3;
-            bh = x + 8 * (s / a.nqb);
-            qb = a.nqb - 1 - (s % a.nqb);
-        } else {
-            bh = id / a.nqb;
-            qb = a.nqb - 1 - (id % a.nqb);
-        }
-    }
+    __shared__ int item_s;
+  for (;;) {                                               // persistent: one (head, row block) item per trip
+    __syncthreads();                                       // everyone is done with the previous item's LDS
+    if (tid == 0) item_s = pop_item(a, blockIdx.x & 7);    // taken only when needed: items are coarse, reserving early hurts the tail
+    __syncthreads();
+    const int item = item_s;
+    if (item < 0) break;
+    const int bh = item >> 16, qb = item & 0xFFFF;
     const int b = bh / a.Hq, h = bh % a.Hq, kvh = h / a.G;
     const int64_t n = a.n, row0 = n - a.n_hat;
     const int64_t blockpos = a.pos0 + (int64_t)qb * BM;                  // multiple of 128
@@ -815,6 +906,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
             a.lse[(int64_t)bh * a.n_hat + (pos - row0)] =
                 l_tot > 0.f ? (m_run * sc2 + log2f(l_tot)) * 0.69314718055994531f : -INFINITY;
     }
+  }                                                        // next item
 }
 
 template <int D>
@@ -829,7 +921,7 @@ static hipError_t launch_prefill_bf16(const PrefillArgs& a, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_bf16_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_bf16_kernel<D>), dim3(a.BH * a.nqb), dim3(PREFILL_THREADS), smem, st, a);
+    hipLaunchKernelGGL((prefill_bf16_kernel<D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
     return hipGetLastError();
 }
 
@@ -846,7 +938,7 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<T, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_kernel<T, D>), dim3(a.BH * a.nqb), dim3(PREFILL_THREADS), smem, st, a);
+    hipLaunchKernelGGL((prefill_kernel<T, D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
     return hipGetLastError();
 }
 
@@ -863,6 +955,13 @@ hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(plan_kernel, dim3(BH), dim3(1024), smem, st, a);
+    return hipGetLastError();
+}
+
+int prefill_block_rows() { return BM; }
+
+hipError_t launch_sched(const SchedArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

@@ -110,20 +110,26 @@ __global__ __launch_bounds__(SCORE_THREADS) void stats_kernel(ScoreArgs a) {
     }
 }
 
-// ---- merge: one thread per row ----------------------------------------------------------------
-__global__ void merge_kernel(ScoreArgs a, int rows) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows) return;
-    const float* p = a.part + (int64_t)i * a.nkb * 2;
+// ---- merge: one wave per row; lanes stride over the key blocks, then a fixed butterfly ------------
+__global__ __launch_bounds__(256) void merge_kernel(ScoreArgs a, int rows) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    const float* p = a.part + (int64_t)row * a.nkb * 2;
     float M = -INFINITY;
-    for (int kb = 0; kb < a.nkb; ++kb) M = fmaxf(M, p[2 * kb]);
+    for (int kb = lane; kb < a.nkb; kb += 64) M = fmaxf(M, p[2 * kb]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
     float L = 0.f;
-    for (int kb = 0; kb < a.nkb; ++kb) {
+    for (int kb = lane; kb < a.nkb; kb += 64) {
         const float m = p[2 * kb];
         if (m != -INFINITY) L += p[2 * kb + 1] * fast_exp2(m - M);
     }
-    a.rowstat[2 * i] = M;
-    a.rowstat[2 * i + 1] = L > 0.f ? 1.0f / L : 0.f;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
+    if (lane == 0) {
+        a.rowstat[2 * row] = M;
+        a.rowstat[2 * row + 1] = L > 0.f ? 1.0f / L : 0.f;
+    }
 }
 
 // ---- pass 2: line sums ------------------------------------------------------------------------
@@ -267,7 +273,7 @@ static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.nkb, a.B * a.Hkv);
     hipLaunchKernelGGL((stats_kernel<T, D>), grid, dim3(SCORE_THREADS), 0, st, a);
     const int rows = a.BH * a.w;
-    hipLaunchKernelGGL(merge_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, a, rows);
+    hipLaunchKernelGGL(merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, a, rows);
     const int wpad = ((a.w + 31) / 32) * 32;
     const size_t smem = (size_t)wpad * (SB + 1) * 4 + (size_t)wpad * 8 + (size_t)wpad * 8;
     hipError_t e;

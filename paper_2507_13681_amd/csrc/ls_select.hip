@@ -244,14 +244,38 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             const uint64_t deadb = __ballot(dead);
             int stop_dead = 64;
             if (early && deadb) stop_dead = __ffsll((unsigned long long)deadb) - 1;
+            // picks 0 .. limit-1 are applied; the running sum is accumulated pick by pick (eight adds per
+            // trip, then one test of the eight partial sums against the target)
+            const int limit = run < stop_dead ? run : stop_dead;
+            const int gbits = __builtin_bit_cast(int, gain);
             int taken = 0;
-            bool exhausted = false;
-            for (int j = 0; j < run; ++j) {
-                if (j == stop_dead) { exhausted = true; break; }
-                sum = __fadd_rn(sum, __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gain), j)));
-                ++taken;
-                if (!(sum < target)) break;
+            bool reached = false;
+            while (taken + 8 <= limit) {
+                float ps[8];
+                float acc = sum;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    acc = __fadd_rn(acc, __builtin_bit_cast(float, __builtin_amdgcn_readlane(gbits, taken + u)));
+                    ps[u] = acc;
+                }
+                int first = 8;
+#pragma unroll
+                for (int u = 7; u >= 0; --u) if (!(ps[u] < target)) first = u;
+                if (first < 8) {
+                    float pick = ps[0];
+#pragma unroll
+                    for (int u = 1; u < 8; ++u) if (first == u) pick = ps[u];
+                    sum = pick; taken += first + 1; reached = true;
+                    break;
+                }
+                sum = acc; taken += 8;
             }
+            while (!reached && taken < limit) {
+                sum = __fadd_rn(sum, __builtin_bit_cast(float, __builtin_amdgcn_readlane(gbits, taken)));
+                ++taken;
+                if (!(sum < target)) reached = true;
+            }
+            const bool exhausted = !reached && stop_dead < run;      // the pick after the last one has no positive gain
             head[which] += taken;
             if (exhausted) { head[0] = n; head[1] = n; done = true; break; }
         }
