@@ -86,7 +86,7 @@ inline int tab_len_of(int64_t n) { return (int)(n / 64) + 4; }
 size_t ws_prefill(const ls_shape* s) {
     const size_t BH = (size_t)s->B * s->Hq;
     const size_t items = BH * (size_t)(s->n / 128 + 2);          // (head, row block) work items, upper bound
-    return up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH) + up(BH * 4) +
+    return up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH) + up(BH * 4) + up(BH * (size_t)(tab_len_of(s->n) + 1) * 2) +
            up(8 * items * 4) + 2 * up(8 * 4);
 }
 size_t ws_compress(const ls_shape* s) {
@@ -208,10 +208,12 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     uint32_t* obits = bp.take<uint32_t>((size_t)BH * words);
     uint8_t* hflag = bp.take<uint8_t>((size_t)BH);
     uint32_t* cost = bp.take<uint32_t>((size_t)BH);
+    uint16_t* pref = bp.take<uint16_t>((size_t)BH * (tab_len + 1));
     const int bm = ls::prefill_block_rows();
     const int64_t pos0 = (s->n - s->n_hat) / bm * bm;
     const int nqb = (int)((s->n - pos0 + bm - 1) / bm);
     if (nqb > 65535) return fail(c, LS_ESHAPE, "ls_sparse_prefill: too many row blocks");
+    if (BH > 8192) return fail(c, LS_ESHAPE, "ls_sparse_prefill: B * Hq exceeds 8192");
     uint32_t* queue = bp.take<uint32_t>(8 * (size_t)BH * nqb);
     int32_t* qlen = bp.take<int32_t>(8);
     int32_t* qhead = bp.take<int32_t>(8);
@@ -220,12 +222,13 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: hipSetDevice failed");
     ls::PlanArgs p{};
     p.n = s->n; p.words = words; p.tab_len = tab_len; p.v_idx = v_idx; p.v_cnt = v_cnt; p.s_idx = s_idx; p.s_cnt = s_cnt;
-    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.tab = tab; p.hflag = hflag; p.cost = cost;
+    p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.tab = tab; p.hflag = hflag; p.cost = cost; p.pref = pref;
     hipError_t e = ls::launch_plan(p, BH, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(plan): %s", hipGetErrorString(e));
     ls::SchedArgs sa{};
     sa.BH = BH; sa.G = s->Hq / s->Hkv; sa.Hq = s->Hq; sa.Hkv = s->Hkv; sa.nqb = nqb; sa.cost = cost;
     sa.queue = queue; sa.qlen = qlen; sa.qhead = qhead;
+    sa.pref = pref; sa.v_cnt = v_cnt; sa.hflag = hflag; sa.tab_len = tab_len; sa.cap_v = cap_v; sa.n = s->n; sa.pos0 = pos0;
     e = ls::launch_sched(sa, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(sched): %s", hipGetErrorString(e));
     ls::PrefillArgs a{};

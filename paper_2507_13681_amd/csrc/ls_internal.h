@@ -49,12 +49,18 @@ struct PlanArgs {
     uint8_t* tab;             // [BH][tab_len]
     uint8_t* hflag;           // [BH]
     uint32_t* cost;           // [BH] estimated tiles per row block (for the work queues)
+    uint16_t* pref;           // [BH][tab_len + 1] prefix counts of table entries with a selected diagonal
 };
 
 // Work queues of the sparse attention kernel: one list of (head, row block) items per XCD.
 struct SchedArgs {
     int BH, G, Hq, Hkv, nqb;
     const uint32_t* cost;     // [BH]
+    const uint16_t* pref;     // [BH][tab_len + 1]
+    const int32_t* v_cnt;     // [BH]
+    const uint8_t* hflag;     // [BH]
+    int tab_len, cap_v;
+    int64_t n, pos0;
     uint32_t* queue;          // [8][BH * nqb] items: bh << 16 | qb
     int32_t* qlen;            // [8]
     int32_t* qhead;           // [8] next item to hand out

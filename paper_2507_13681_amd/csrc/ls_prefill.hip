@@ -98,32 +98,49 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
         if (total_bits == (int)n) nv = 0;
         a.cost[bh] = (uint32_t)(active_entries + (nv + 63) / 64 + 1);
     }
+    // prefix counts of active entries: pref[e] = number of active entries below e
+    __syncthreads();
+    __shared__ uint32_t cnt[1024];                         // per-thread chunk totals
+    const int chunk = (a.tab_len + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int e0 = tid * chunk, e1 = (e0 + chunk < a.tab_len) ? e0 + chunk : a.tab_len;
+    int mine2 = 0;
+    for (int e = e0; e < e1; ++e) mine2 += a.tab[(int64_t)bh * a.tab_len + e] & 1;
+    cnt[tid] = mine2;
+    __syncthreads();
+    if (tid == 0) { uint32_t run = 0; for (int i = 0; i < (int)blockDim.x; ++i) { const uint32_t t = cnt[i]; cnt[i] = run; run += t; } }
+    __syncthreads();
+    uint32_t run = cnt[tid];
+    uint16_t* pref = a.pref + (int64_t)bh * (a.tab_len + 1);
+    for (int e = e0; e < e1; ++e) { pref[e] = (uint16_t)run; run += a.tab[(int64_t)bh * a.tab_len + e] & 1; }
+    if (e1 == a.tab_len && e0 < a.tab_len) pref[a.tab_len] = (uint16_t)run;
 }
 
 // ---------------------------------------------------------------------------------------------
 // sched: builds the 8 work queues.  The query heads of one KV head stay together (they share K/V
 // tiles in one L2); KV groups are dealt to the XCDs heaviest first, each to the XCD with the least
-// work so far.  Inside a queue later row blocks come first and the G heads of a group are adjacent.
-// One workgroup; groups beyond SCHED_MAX_GROUPS fall back to round-robin dealing.
+// work so far.
+// One workgroup per queue; groups beyond SCHED_MAX_GROUPS fall back to round-robin dealing.  Inside a
+// queue items are ordered by decreasing tile count, so the long ones start first.
 // ---------------------------------------------------------------------------------------------
 constexpr int SCHED_MAX_GROUPS = 2048;
-__global__ __launch_bounds__(256) void sched_kernel(SchedArgs a) {
+constexpr int SCHED_MAX_HEADS = 8192;      // heads one XCD's queue can take
+constexpr int SCHED_THREADS = 1024;
+__global__ __launch_bounds__(SCHED_THREADS) void sched_kernel(SchedArgs a) {
     __shared__ uint32_t gcost[SCHED_MAX_GROUPS];
     __shared__ uint16_t order[SCHED_MAX_GROUPS];          // groups by decreasing cost
-    __shared__ uint16_t bin_of[SCHED_MAX_GROUPS], slot_of[SCHED_MAX_GROUPS];
-    __shared__ int bin_groups[8];
+    __shared__ uint16_t bin_of[SCHED_MAX_GROUPS];
     const int tid = threadIdx.x;
     const int groups = a.BH / a.G;
     const bool sorted = groups <= SCHED_MAX_GROUPS;
-    if (sorted) {
-        for (int gi = tid; gi < groups; gi += 256) {
+    if (sorted) {                                          // every block repeats this small computation
+        for (int gi = tid; gi < groups; gi += SCHED_THREADS) {
             const int b = gi / a.Hkv, kvh = gi % a.Hkv;
             uint32_t c = 0;
             for (int g = 0; g < a.G; ++g) c += a.cost[b * a.Hq + kvh * a.G + g];
             gcost[gi] = c;
         }
         __syncthreads();
-        for (int gi = tid; gi < groups; gi += 256) {       // rank sort (ties: smaller index first)
+        for (int gi = tid; gi < groups; gi += SCHED_THREADS) {   // rank sort (ties: smaller index first)
             const uint32_t c = gcost[gi];
             int rank = 0;
             for (int o = 0; o < groups; ++o) { const uint32_t d = gcost[o]; rank += (d > c) || (d == c && o < gi); }
@@ -131,38 +148,61 @@ __global__ __launch_bounds__(256) void sched_kernel(SchedArgs a) {
         }
         __syncthreads();
         if (tid == 0) {
-            uint64_t load[8]; int cnt[8];
-            for (int x = 0; x < 8; ++x) { load[x] = 0; cnt[x] = 0; }
+            uint64_t load[8];
+            for (int x = 0; x < 8; ++x) load[x] = 0;
             for (int r = 0; r < groups; ++r) {
                 const int gi = order[r];
                 int best = 0;
                 for (int x = 1; x < 8; ++x) if (load[x] < load[best]) best = x;
-                bin_of[gi] = (uint16_t)best; slot_of[gi] = (uint16_t)cnt[best];
-                load[best] += gcost[gi] + 1; ++cnt[best];
+                bin_of[gi] = (uint16_t)best;
+                load[best] += gcost[gi] + 1;
             }
-            for (int x = 0; x < 8; ++x) bin_groups[x] = cnt[x];
         }
         __syncthreads();
     }
-    const int per_bin_rr = (groups + 7) / 8;
-    // item (gi, g, qb) -> queue bin, position (nqb-1-qb) * (groups in bin * G) + slot * G + g
-    const int64_t total = (int64_t)a.BH * a.nqb;
-    const int64_t qcap = total;
-    for (int64_t it = tid; it < total; it += 256) {
-        const int bh = (int)(it / a.nqb), qb = (int)(it % a.nqb);
-        const int b = bh / a.Hq, h = bh % a.Hq, gi = b * a.Hkv + h / a.G, g = h % a.G;
-        int bin, slot, ng;
-        if (sorted) { bin = bin_of[gi]; slot = slot_of[gi]; ng = bin_groups[bin]; }
-        else { bin = gi & 7; slot = gi >> 3; ng = (groups - bin + 7) / 8; }
-        (void)per_bin_rr;
-        const int64_t posn = (int64_t)(a.nqb - 1 - qb) * ng * a.G + (int64_t)slot * a.G + g;
-        a.queue[(int64_t)bin * qcap + posn] = ((uint32_t)bh << 16) | (uint32_t)qb;
+    // Work items (head, row block) of this block's bin, heaviest first.  Item cost = key blocks with a
+    // selected diagonal that the row block visits (from the prefix counts) + packed column tiles.
+    __shared__ uint32_t hist[4097];
+    __shared__ uint16_t heads[SCHED_MAX_HEADS];
+    __shared__ int nheads;
+    const int x = blockIdx.x;
+    const int64_t qcap = (int64_t)a.BH * a.nqb;
+    auto item_cost = [&](int bh, int qb) -> int {
+        const int64_t blockpos = a.pos0 + (int64_t)qb * BM;
+        const int64_t posmax = (blockpos + BM - 1 < a.n - 1) ? blockpos + BM - 1 : a.n - 1;
+        const int jb = (int)(blockpos / BN), kb_hi = (int)(posmax / BN);
+        const uint16_t* pref = a.pref + (int64_t)bh * (a.tab_len + 1);
+        int c = pref[jb + 2] - pref[jb - kb_hi + 1];      // entries jb-kb_hi+1 .. jb+1
+        int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
+        if (a.hflag[bh] & 1) nv = 0;
+        c += (nv + 63) / 64;
+        return c > 4095 ? 4095 : c;
+    };
+    for (int i = tid; i < 4097; i += SCHED_THREADS) hist[i] = 0u;
+    if (tid == 0) nheads = 0;
+    __syncthreads();
+    for (int bh = tid; bh < a.BH; bh += SCHED_THREADS) {   // heads of this bin (order inside the list is free)
+        const int b = bh / a.Hq, h = bh % a.Hq, gi = b * a.Hkv + h / a.G;
+        const int bin = sorted ? (int)bin_of[gi] : (gi & 7);
+        if (bin == x) { const int i = atomicAdd(&nheads, 1); if (i < SCHED_MAX_HEADS) heads[i] = (uint16_t)bh; }
     }
-    if (tid < 8) {
-        const int ng = sorted ? bin_groups[tid] : (groups - tid + 7) / 8;
-        a.qlen[tid] = ng * a.G * a.nqb;
-        a.qhead[tid] = 0;
+    __syncthreads();
+    const int nh_ = nheads < SCHED_MAX_HEADS ? nheads : SCHED_MAX_HEADS;
+    const int64_t items = (int64_t)nh_ * a.nqb;
+    for (int64_t it = tid; it < items; it += SCHED_THREADS)
+        atomicAdd(&hist[4095 - item_cost(heads[it / a.nqb], (int)(it % a.nqb))], 1u);
+    __syncthreads();
+    if (tid == 0) {                                        // exclusive scan in decreasing-cost order
+        uint32_t run = 0;
+        for (int i = 0; i < 4096; ++i) { const uint32_t t = hist[i]; hist[i] = run; run += t; }
     }
+    __syncthreads();
+    for (int64_t it = tid; it < items; it += SCHED_THREADS) {
+        const int bh = heads[it / a.nqb], qb = (int)(it % a.nqb);
+        const uint32_t posn = atomicAdd(&hist[4095 - item_cost(bh, qb)], 1u);
+        a.queue[(int64_t)x * qcap + posn] = ((uint32_t)bh << 16) | (uint32_t)qb;
+    }
+    if (tid == 0) { a.qlen[x] = (int)items; a.qhead[x] = 0; }
 }
 
 // Persistent launch: enough workgroups to fill the chip at any occupancy this kernel reaches
@@ -961,7 +1001,7 @@ hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st) {
 int prefill_block_rows() { return BM; }
 
 hipError_t launch_sched(const SchedArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(sched_kernel, dim3(1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(sched_kernel, dim3(8), dim3(SCHED_THREADS), 0, st, a);
     return hipGetLastError();
 }
 
