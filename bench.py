@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_FP32_MFMA_TFLOPS = 157.3
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/prefill_bf16_kernel_multiturn_32k_counters.md (scaled by the copy-probe factors 2.00 / 1.00).
+# Counters cannot be read inside a timed run, so this is the recorded figure for the default workload only.
+MEASURED_TRAFFIC_BYTES = {("multiturn_32k", 0.95): 2.05e9}
 
 
 def per_row_cells(n, n_hat, rows_a, v_sel, s_sel):
@@ -50,6 +54,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (see profiles/)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of MIB MiB (10 launches): calibrates the rocprofv3 FETCH_SIZE / "
+                         "WRITE_SIZE counters against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by KV-head group with no "
@@ -58,6 +65,15 @@ def main():
 
     import torch
     from paper_2507_13681_amd import binding, inputs, metrics
+
+    if args.copy_probe:
+        x = torch.empty(args.copy_probe << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        y = torch.empty_like(x)
+        for _ in range(10):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": x.numel(), "copy_probe_bytes_written": x.numel(), "launches": 10}))
+        return
 
     cfg = inputs.CONFIGS[args.workload]
     alpha = cfg.alpha if args.alpha is None else args.alpha
@@ -144,7 +160,7 @@ def main():
         "ms_per_call": {a: round(b, 4) for a, b in br.items()},
         "wall_s": round(wall, 3),
         "roofline": {"kernel": "prefill_bf16_kernel" if cfg.dtype == "bf16" else "prefill_kernel", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get((cfg.name, alpha)),
                      "kernel_ms": round(kern_ms, 4), "launches": launches},
         "paper_context": "no speed-up printed in the paper's text; its machine: 1x H100 80GB + 8-core Xeon Gold 6542Y",
     }
