@@ -589,33 +589,54 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
 // ---------------------------------------------------------------------------------------------
 // bf16 kernel: same tile sequence, masks and softmax as prefill_kernel, but staged the CDNA4 way.
 //   * K and V rows go straight from global memory into LDS (global_load_lds, 16 bytes per lane, no
-//     registers, no LDS store instructions).  A lane's 16 bytes land at LDS base + 16 * lane, so a
-//     tile is laid out as consecutive 16-byte slots: 64 K rows of KS slots (row bytes + one pad
-//     slot) followed by 64 V rows of VS slots (row bytes + four pad slots); the lane that owns a pad
-//     slot simply does not load.
+//     registers, no LDS store instructions).  A lane's 16 bytes land at LDS base + 16 * lane, so one
+//     wave-wide transfer fills 1024 consecutive bytes: RPI whole rows of DS 16-byte slots.  Where a
+//     lane's bytes land is fixed; which bytes it fetches is free, so slot s of row r receives chunk
+//     s ^ swizzle(r) of that row.  The swizzles (kswz, vswz) are chosen so that the fragment reads
+//     below touch every LDS bank once per pass; for d = 128 the K transfers are also spaced 64 bytes
+//     apart.  All transfers of a wave then differ only in a uniform base address: one per-lane
+//     offset register per operand serves the whole kernel.
 //   * V stays row-major; the V^T fragments of the P*V product come from the LDS transpose read
 //     ds_read_b64_tr_b16: in a block of 16 lanes, lane s addresses 4 consecutive 16-bit values and
 //     lane L receives value L%4 of the lanes L/4, L/4+4, L/4+8, L/4+12.  With lane s pointing at key
 //     (s/4) and at d-offset 4*(s%4), lane L ends up with four keys of column d = L: two reads give the
 //     eight keys of a fragment.
-// Slots of rows that do not exist (tail of the context or of the column list) re-load an existing row;
-// their keys are masked, so only finiteness of the staged values matters.
+// Rows that do not exist (tail of the context or of the column list) re-load an existing row; their
+// keys are masked, so only finiteness of the staged values matters.
 // ---------------------------------------------------------------------------------------------
 template <int D>
 struct DirectCfg {
+    static_assert(D == 128 || D == 64, "head dimension");
     static constexpr int RB = D * 2;                      // bytes per row
-    static constexpr int DS = RB / 16;                    // data slots per row
-    static constexpr int KS = DS + 1;                     // K row: conflict-free 16-byte fragment reads
-    static constexpr int VS = DS + 4;                     // V row: stride = 16 banks mod 64 for the transpose reads
-    static constexpr int K_STRIDE = 16 * KS, V_STRIDE = 16 * VS;
-    static constexpr int K_SLOTS = BN * KS, V_SLOTS = BN * VS, SLOTS = K_SLOTS + V_SLOTS;
-    static constexpr int LOADS = (SLOTS + 63) / 64;       // wave-wide load instructions per tile
-    static constexpr int LPW = (LOADS + 3) / 4;           // ... per wave
-    static constexpr int TILE_BYTES = LOADS * 1024;       // one buffer (rounded up to whole instructions)
+    static constexpr int DS = RB / 16;                    // 16-byte slots per row
+    static constexpr int RPI = 64 / DS;                   // rows per transfer instruction
+    static constexpr int NI = BN / RPI;                   // transfer instructions per operand tile
+    static constexpr int IPW = NI / 4;                    // ... per wave
+    static constexpr int K_ISTR = D == 128 ? 1088 : 1024; // LDS bytes from one K transfer to the next
+    static constexpr int V_ISTR = 1024;
+    static constexpr int K_BYTES = NI * K_ISTR, V_BYTES = NI * V_ISTR, TILE_BYTES = K_BYTES + V_BYTES;
+    static constexpr int STEP = 4 * RPI * RB;             // global bytes between a wave's consecutive transfers
     static constexpr int KSTEPS = D / 16, DBLK = D / 32;
+    static constexpr int KA = D == 128 ? 2 : 4;           // K fragment address registers
+    // slot swizzles (XOR on the 16-byte slot index inside a row); both are unchanged by adding a
+    // multiple of 16 (d = 128) or 32 (d = 64) to the row
+    __device__ static constexpr int kswz(int row) { return D == 128 ? (row & 3) : (((row >> 1) & 3) | (((row >> 3) & 1) << 2)); }
+    __device__ static constexpr int vswz(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// One wave-wide global -> LDS transfer: lane l fetches the 16 bytes at gbase + voff and they land at
+// LDS byte address lds + 16 * l.  gbase and lds are wave-uniform.  Written as an asm statement so that
+// the compiler does not count the transfer among the memory operations it tracks: it cannot tell which
+// LDS bytes a transfer fills and would make every later LDS read wait for all outstanding transfers,
+// serialising the prefetch of the next tile with the products of the current one.  The kernel waits
+// for its transfers itself (wait_transfers before the barrier that publishes a buffer).  M0 is used by
+// nothing else in these kernels.
+__device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void wait_transfers() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int D>
 __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(PrefillArgs a) {
@@ -627,16 +648,44 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
     int32_t* colring = reinterpret_cast<int32_t*>(ob + a.words + 1);     // [3][64]; ob = zero word + bitmap
     int32_t* wcnt = colring + 192;                                       // [8]
     uint16_t* kbl = reinterpret_cast<uint16_t*>(wcnt + 8);               // [tab_len] active key blocks | flags << 14
+    uint8_t* tab = reinterpret_cast<uint8_t*>(kbl + ((a.tab_len + 7) & ~7));   // [tab_len] this head's per-j table
+    const uint32_t tiles_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)tiles;
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r32 = lane & 31, g = lane >> 5;
+
+    // ---- per-lane constants of the transfers: this lane fills slot sl of row rowlane (+ 4*RPI per
+    // further instruction of the wave) and fetches the chunk the swizzle assigns to that slot
+    const int rowlane = C::RPI * wv + lane / C::DS;
+    const int sl = lane % C::DS;
+    const uint32_t kcpart = 16u * (uint32_t)(sl ^ C::kswz(rowlane));
+    const uint32_t vcpart = 16u * (uint32_t)(sl ^ C::vswz(rowlane));
+    const uint32_t kvoff0 = (uint32_t)rowlane * C::RB + kcpart, vvoff0 = (uint32_t)rowlane * C::RB + vcpart;
+    // ---- K fragment reads: row r32 (+32), chunk 2c+g sits in slot (2c+g) ^ kswz
+    int kaddr[C::KA];
+    {
+        const int x = C::kswz(r32);
+        const int krow = (r32 / C::RPI) * C::K_ISTR + (r32 % C::RPI) * C::RB;
+#pragma unroll
+        for (int j = 0; j < C::KA; ++j) kaddr[j] = krow + 32 * (j ^ (x >> 1)) + 16 * (g ^ (x & 1));
+    }
+    // ---- V^T fragment reads (see the header comment): key 4g + L16/4 (+8, +16 q4), 64-byte block i
+    int vaddr[C::DBLK];
+    {
+        const int L16 = lane & 15, beta = (lane >> 4) & 1;
+        const int lrow = 4 * g + (L16 >> 2);
+        const int y = C::vswz(lrow) >> 2;
+#pragma unroll
+        for (int i = 0; i < C::DBLK; ++i) vaddr[i] = C::K_BYTES + lrow * C::RB + 64 * (i ^ y) + 32 * beta + 8 * (L16 & 3);
+    }
 
     __shared__ int item_s;
   for (;;) {                                               // persistent: one (head, row block) item per trip
     __syncthreads();                                       // everyone is done with the previous item's LDS
     if (tid == 0) item_s = pop_item(a, blockIdx.x & 7);    // taken only when needed: items are coarse, reserving early hurts the tail
     __syncthreads();
-    const int item = item_s;
+    const int item = __builtin_amdgcn_readfirstlane(item_s);
     if (item < 0) break;
     const int bh = item >> 16, qb = item & 0xFFFF;
     const int b = bh / a.Hq, h = bh % a.Hq, kvh = h / a.G;
@@ -650,6 +699,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
 
     for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i + 1] = a.obits[(int64_t)bh * a.words + i];
     if (tid == 0) ob[0] = 0u;
+    for (int i = tid; i < a.tab_len; i += PREFILL_THREADS) tab[i] = tabg[i];
     const int64_t pos = blockpos + 32 * wv + r32;
     const bool row_ok = (pos >= row0) && (pos < n);
     Frag<T> qf[C::KSTEPS];
@@ -680,6 +730,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
         n1 += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
         __syncthreads();
     }
+    n1 = __builtin_amdgcn_readfirstlane(n1);
     int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
     const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
     if (a.hflag[bh] & 1) nv = 0;                           // every diagonal is selected: phase 1 covers all cells
@@ -698,14 +749,13 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
         for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;                  // m_run in raw logit units
     const float sc2 = a.scale_log2e;
+    // The running reference m_run follows the row maximum lazily: it moves only when a tile exceeds it
+    // by more than 2^8 in the exponent, so probabilities stay below 256 (exact in fp32 and bf16 alike)
+    // and most tiles need no rescaling of the accumulators.
+    const float lazy = 8.0f / sc2;
 
-    // per-lane constant part of the transpose-read address (see the header comment)
-    const int L16 = lane & 15, beta = (lane >> 4) & 1;
-    const int vlane_off = (4 * g + (L16 >> 2)) * C::V_STRIDE + (16 * beta + 4 * (L16 & 3)) * 2;
-
-    auto process = [&](const unsigned char* tile, uint32_t am0, uint32_t am1, bool full) {
-        const unsigned char* kt = tile;
-        const unsigned char* vt = tile + C::K_SLOTS * 16;
+    auto process = [&](int tileoff, uint32_t am0, uint32_t am1, bool full) {
+        const unsigned char* tile = tiles + tileoff;
         f32x16 s[2];
         bool act[2];
         act[0] = __ballot(am0 != 0u) != 0ull;
@@ -713,13 +763,16 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
         if (!act[0] && !act[1]) return;
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         s[0] = zero16; s[1] = zero16;
+        constexpr int SUB = (32 / C::RPI) * C::K_ISTR;     // LDS bytes from key r to key r + 32
         if (act[0] && act[1]) {
             // 2 * KSTEPS products; K fragments are fetched RING_S steps ahead of their use
             constexpr int NP = 2 * C::KSTEPS;
-            const unsigned char* kbase = kt + r32 * C::K_STRIDE + 16 * g;
             Frag<T> kf[NP];
 #pragma unroll
-            for (int i = 0; i < NP; ++i) load_frag(kf[i], kbase + (i & 1) * 32 * C::K_STRIDE + 32 * (i >> 1));
+            for (int i = 0; i < NP; ++i) {
+                const int c = i >> 1;
+                load_frag(kf[i], tile + kaddr[c & (C::KA - 1)] + (i & 1) * SUB + 32 * (c & ~(C::KA - 1)));
+            }
 #pragma unroll
             for (int i = 0; i < NP; ++i) mma(s[i & 1], kf[i], qf[i >> 1]);   // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
 #if LS_RING_S > 0
@@ -735,11 +788,10 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
                 if (!act[sub]) continue;
-                const unsigned char* krow = kt + (32 * sub + r32) * C::K_STRIDE + 16 * g;
 #pragma unroll
                 for (int c = 0; c < C::KSTEPS; ++c) {
                     Frag<T> kf;
-                    load_frag(kf, krow + 32 * c);
+                    load_frag(kf, tile + kaddr[c & (C::KA - 1)] + sub * SUB + 32 * (c & ~(C::KA - 1)));
                     mma(s[sub], kf, qf[c]);
                 }
             }
@@ -764,7 +816,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
             }
         }
         mx = fmaxf(mx, xor32(mx));
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = (mx > m_run + lazy) ? mx : m_run;            // -inf + lazy = -inf: the first finite tile always moves it
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float corr = fast_exp2((m_run - m_safe) * sc2);
         const float mneg = -m_safe * sc2;
@@ -786,112 +838,96 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
                 for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
         }
         auto vt_frag = [&](Frag<T>& vf, int q4, int i) {     // V^T fragment: keys 16*q4.., output block i
-            const unsigned char* va = vt + vlane_off + 16 * q4 * C::V_STRIDE + 64 * i;
+            const unsigned char* va = tile + vaddr[i] + 16 * q4 * C::RB;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::V_STRIDE));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::RB));
             struct U { s16x4 a, b; } u = {lo, hi};
             vf.v = __builtin_bit_cast(bf16x8, u);
         };
-        {
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {              // 16-key chunk q4: keys 16*q4 .. 16*q4+15 of the tile
-                if (!act[q4 >> 1]) continue;
-                float pv[8];
+        for (int q4 = 0; q4 < 4; ++q4) {                  // 16-key chunk q4: keys 16*q4 .. 16*q4+15 of the tile
+            if (!act[q4 >> 1]) continue;
+            float pv[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pv[e] = s[q4 >> 1][8 * (q4 & 1) + e];
-                Frag<T> pf;
-                pack_frag(pf, pv);
+            for (int e = 0; e < 8; ++e) pv[e] = s[q4 >> 1][8 * (q4 & 1) + e];
+            Frag<T> pf;
+            pack_frag(pf, pv);
 #pragma unroll
-                for (int i = 0; i < C::DBLK; ++i) {
-                    Frag<T> vf;
-                    vt_frag(vf, q4, i);
-                    mma(oacc[i], vf, pf);
-                }
+            for (int i = 0; i < C::DBLK; ++i) {
+                Frag<T> vf;
+                vt_frag(vf, q4, i);
+                mma(oacc[i], vf, pf);
             }
         }
     };
 
-    // ---- staging: wave wv issues load instructions q = wv + 4*i; instruction q fills slots 64q .. 64q+63.
-    // Instructions 0 .. K_LOADS-1 carry K rows, the rest V rows (both slot counts are multiples of 64).
-    // A pad slot re-loads chunk 0 of its row, a row beyond the context re-loads the last row, a missing
+    // ---- staging: wave wv issues transfer instructions wv, wv+4, ... of each operand; instruction q
+    // carries tile rows RPI*q .. RPI*q+RPI-1.  A row beyond the context re-loads the last row, a missing
     // column re-loads row 0: every slot is always written with finite data and needs no exec masking.
-    constexpr int K_LOADS = C::K_SLOTS / 64;
-    static_assert(C::K_SLOTS % 64 == 0 && C::V_SLOTS % 64 == 0, "slot counts must be whole instructions");
-    int srow[C::LPW];                                      // tile row of this lane's slot in instruction i
-    uint32_t soff[C::LPW];                                 // row * RB + 16 * chunk
-#pragma unroll
-    for (int i = 0; i < C::LPW; ++i) {
-        const int q = wv + 4 * i;
-        const int slot = q * 64 + lane;
-        int row, c;
-        if (q < K_LOADS) { row = slot / C::KS; c = slot % C::KS; }
-        else { const int s2 = slot - C::K_SLOTS; row = s2 / C::VS; c = s2 % C::VS; }
-        if (c >= C::DS) c = 0;
-        if (row > BN - 1) row = BN - 1;                    // instructions past the tile are never issued
-        srow[i] = row;
-        soff[i] = (uint32_t)(row * C::RB + 16 * c);
-    }
     auto issue = [&](int t) {                              // global -> LDS buffer t & 1 for tile t
-        unsigned char* dst = tiles + (t & 1) * C::TILE_BYTES;
+        const uint32_t dst = tiles_lds + (uint32_t)((t & 1) * C::TILE_BYTES);
+        const uint32_t kdst = dst + (uint32_t)(wv * C::K_ISTR), vdst = dst + (uint32_t)(C::K_BYTES + wv * C::V_ISTR);
         if (t < n1) {
-            const int64_t key0 = (int64_t)(kbl[t] & 0x3FFF) * BN;
+            const int64_t key0 = (int64_t)(__builtin_amdgcn_readfirstlane((int)kbl[t]) & 0x3FFF) * BN;
             const unsigned char* kb_ = Kg + key0 * C::RB;
             const unsigned char* vb_ = Vg + key0 * C::RB;
             if (key0 + BN <= n) {
 #pragma unroll
-                for (int i = 0; i < C::LPW; ++i) {
-                    const int q = wv + 4 * i;
-                    if (q < C::LOADS)
-                        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)((q < K_LOADS ? kb_ : vb_) + soff[i]),
-                                                         (void __attribute__((address_space(3)))*)(dst + q * 1024), 16, 0, 0);
-                }
+                for (int i = 0; i < C::IPW; ++i) dma16(kb_ + i * C::STEP, kvoff0, kdst + (uint32_t)(4 * i * C::K_ISTR));
+#pragma unroll
+                for (int i = 0; i < C::IPW; ++i) dma16(vb_ + i * C::STEP, vvoff0, vdst + (uint32_t)(4 * i * C::V_ISTR));
             } else {                                       // last key block of the context: clamp the rows
                 const int last = (int)(n - 1 - key0);
 #pragma unroll
-                for (int i = 0; i < C::LPW; ++i) {
-                    const int q = wv + 4 * i;
-                    const uint32_t off = srow[i] <= last ? soff[i] : soff[i] - (uint32_t)((srow[i] - last) * C::RB);
-                    if (q < C::LOADS)
-                        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)((q < K_LOADS ? kb_ : vb_) + off),
-                                                         (void __attribute__((address_space(3)))*)(dst + q * 1024), 16, 0, 0);
+                for (int i = 0; i < C::IPW; ++i) {
+                    const int row = rowlane + 4 * C::RPI * i;
+                    const uint32_t ro = (uint32_t)(row <= last ? row : last) * C::RB;
+                    dma16(kb_, ro + kcpart, kdst + (uint32_t)(4 * i * C::K_ISTR));
+                    dma16(vb_, ro + vcpart, vdst + (uint32_t)(4 * i * C::V_ISTR));
                 }
             }
         } else {
             const int32_t* cols = colring + (t % 3) * BN;
 #pragma unroll
-            for (int i = 0; i < C::LPW; ++i) {
-                const int q = wv + 4 * i;
-                int32_t col = cols[srow[i]];
+            for (int i = 0; i < C::IPW; ++i) {
+                int32_t col = cols[rowlane + 4 * C::RPI * i];
                 if (col < 0) col = 0;
-                const uint32_t off = (uint32_t)col * C::RB + (soff[i] - (uint32_t)(srow[i] * C::RB));
-                if (q < C::LOADS)
-                    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)((q < K_LOADS ? Kg : Vg) + off),
-                                                     (void __attribute__((address_space(3)))*)(dst + q * 1024), 16, 0, 0);
+                const uint32_t ro = (uint32_t)col * C::RB;
+                dma16(Kg, ro + kcpart, kdst + (uint32_t)(4 * i * C::K_ISTR));
+                dma16(Vg, ro + vcpart, vdst + (uint32_t)(4 * i * C::V_ISTR));
             }
         }
     };
-    auto put_cols = [&](int t) {                           // column ids of gathered tile t -> LDS (read when t is issued / masked)
+    // column ids of gathered tile t: fetched into a register one iteration before they are written to
+    // LDS (slot t % 3), which happens one iteration before tile t is issued.  The global load is thus
+    // never waited for while transfers are in flight.
+    auto fetch_cols = [&](int t) -> int32_t {
         if (t >= n1 && t < ntiles && tid < BN) {
             const int idx = (t - n1) * BN + tid;
-            colring[(t % 3) * BN + tid] = idx < nv ? vi[idx] : -1;
+            return idx < nv ? vi[idx] : -1;
         }
+        return -1;
+    };
+    auto store_cols = [&](int t, int32_t c) {
+        if (t >= n1 && t < ntiles && tid < BN) colring[(t % 3) * BN + tid] = c;
     };
 
-    __syncthreads();                                       // zeroed buffers, bitmap, kbl visible
-    put_cols(0);
-    put_cols(1);
-    __syncthreads();
+    store_cols(0, fetch_cols(0));
+    store_cols(1, fetch_cols(1));
+    int32_t colpre = fetch_cols(2);
+    __syncthreads();                                       // bitmap, table, kbl, first column ids visible
     if (ntiles > 0) issue(0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
+    wait_transfers();
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
+        store_cols(t + 2, colpre);
+        colpre = fetch_cols(t + 3);
         if (t + 1 < ntiles) issue(t + 1);
-        put_cols(t + 2);
         uint32_t am0 = 0u, am1 = 0u;
         bool full = false;
         if (t < n1) {
-            const int e = kbl[t];
+            const int e = __builtin_amdgcn_readfirstlane((int)kbl[t]);
             const int64_t key0 = (int64_t)(e & 0x3FFF) * BN;
             const bool fullflag = (e >> 14) & 1;
             if (!row_ok) { am0 = am1 = 0u; }
@@ -907,7 +943,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
             const int base = (t - n1) * BN;
             const int cnt = nv - base < BN ? nv - base : BN;
             const int32_t mycol = lane < cnt ? cols[lane] : 0;
-            const uint8_t f = lane < cnt ? tabg[jb - (mycol >> 6) + 1] : (uint8_t)3;
+            const uint8_t f = lane < cnt ? tab[jb - (mycol >> 6) + 1] : (uint8_t)3;
             const uint64_t drop = __ballot(f == 3);        // wholly covered by phase 1 (or no such slot)
             const uint64_t chk = __ballot(f == 1);         // partly covered: test cell by cell
             uint64_t am = 0ull;
@@ -925,8 +961,8 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
             }
             am0 = (uint32_t)am; am1 = (uint32_t)(am >> 32);
         }
-        process(tiles + (t & 1) * C::TILE_BYTES, am0, am1, full);
-        __builtin_amdgcn_s_waitcnt(0x0F70);                // this wave's loads of tile t+1 have landed
+        process((t & 1) * C::TILE_BYTES, am0, am1, full);
+        wait_transfers();                                  // this wave's transfers of tile t+1 have landed
         __syncthreads();
     }
 
@@ -952,7 +988,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
 template <int D>
 static size_t prefill_bf16_smem(int words, int tab_len) {
     return 2 * (size_t)DirectCfg<D>::TILE_BYTES + (size_t)(words + 1) * 4 + 192 * 4 + 8 * 4 +
-           (size_t)((tab_len + 7) & ~7) * 2 + 16;
+           (size_t)((tab_len + 7) & ~7) * 2 + (size_t)tab_len + 16;
 }
 
 template <int D>
