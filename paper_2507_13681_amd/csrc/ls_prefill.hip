@@ -27,7 +27,10 @@
 namespace ls {
 
 #ifndef LS_RING_S
-#define LS_RING_S 4       // K fragments in flight ahead of the QK^T products (0: leave the order to the compiler)
+#define LS_RING_S 4       // K fragments in flight ahead of the QK^T products
+#endif
+#ifndef LS_RING_P
+#define LS_RING_P 3       // V^T fragments in flight ahead of the P*V products
 #endif
 constexpr int BM = 128;   // query rows per workgroup
 constexpr int BN = 64;    // keys per tile
@@ -754,116 +757,12 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
     // and most tiles need no rescaling of the accumulators.
     const float lazy = 8.0f / sc2;
 
-    auto process = [&](int tileoff, uint32_t am0, uint32_t am1, bool full) {
-        const unsigned char* tile = tiles + tileoff;
-        f32x16 s[2];
-        bool act[2];
-        act[0] = __ballot(am0 != 0u) != 0ull;
-        act[1] = __ballot(am1 != 0u) != 0ull;
-        if (!act[0] && !act[1]) return;
-        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        s[0] = zero16; s[1] = zero16;
-        constexpr int SUB = (32 / C::RPI) * C::K_ISTR;     // LDS bytes from key r to key r + 32
-        if (act[0] && act[1]) {
-            // 2 * KSTEPS products; K fragments are fetched RING_S steps ahead of their use
-            constexpr int NP = 2 * C::KSTEPS;
-            Frag<T> kf[NP];
-#pragma unroll
-            for (int i = 0; i < NP; ++i) {
-                const int c = i >> 1;
-                load_frag(kf[i], tile + kaddr[c & (C::KA - 1)] + (i & 1) * SUB + 32 * (c & ~(C::KA - 1)));
-            }
-#pragma unroll
-            for (int i = 0; i < NP; ++i) mma(s[i & 1], kf[i], qf[i >> 1]);   // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
-#if LS_RING_S > 0
-            __builtin_amdgcn_sched_group_barrier(0x100, LS_RING_S, 0);
-#pragma unroll
-            for (int i = 0; i < NP - LS_RING_S; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, LS_RING_S, 0);
-#endif
-        } else {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                if (!act[sub]) continue;
-#pragma unroll
-                for (int c = 0; c < C::KSTEPS; ++c) {
-                    Frag<T> kf;
-                    load_frag(kf, tile + kaddr[c & (C::KA - 1)] + sub * SUB + 32 * (c & ~(C::KA - 1)));
-                    mma(s[sub], kf, qf[c]);
-                }
-            }
-        }
-        float mx = -INFINITY;
-        if (full) {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
-        } else {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const uint32_t am = sub ? am1 : am0;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kbit = 8 * (r >> 2) + 4 * g + (r & 3);
-                    const float x = ((am >> kbit) & 1u) ? s[sub][r] : -INFINITY;
-                    s[sub][r] = x;
-                    mx = fmaxf(mx, x);
-                }
-            }
-        }
-        mx = fmaxf(mx, xor32(mx));
-        const float m_new = (mx > m_run + lazy) ? mx : m_run;            // -inf + lazy = -inf: the first finite tile always moves it
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float corr = fast_exp2((m_run - m_safe) * sc2);
-        const float mneg = -m_safe * sc2;
-        m_run = m_new;
-        float ps4[4] = {0.f, 0.f, 0.f, 0.f};               // four short add chains instead of one long one
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(__builtin_fmaf(s[sub][r], sc2, mneg));
-                s[sub][r] = p;
-                ps4[r & 3] += p;
-            }
-        l_run = l_run * corr + ((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
-        if (__ballot(corr != 1.0f) != 0ull) {
-#pragma unroll
-            for (int i = 0; i < C::DBLK; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
-        }
-        auto vt_frag = [&](Frag<T>& vf, int q4, int i) {     // V^T fragment: keys 16*q4.., output block i
-            const unsigned char* va = tile + vaddr[i] + 16 * q4 * C::RB;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::RB));
-            struct U { s16x4 a, b; } u = {lo, hi};
-            vf.v = __builtin_bit_cast(bf16x8, u);
-        };
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {                  // 16-key chunk q4: keys 16*q4 .. 16*q4+15 of the tile
-            if (!act[q4 >> 1]) continue;
-            float pv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pv[e] = s[q4 >> 1][8 * (q4 & 1) + e];
-            Frag<T> pf;
-            pack_frag(pf, pv);
-#pragma unroll
-            for (int i = 0; i < C::DBLK; ++i) {
-                Frag<T> vf;
-                vt_frag(vf, q4, i);
-                mma(oacc[i], vf, pf);
-            }
-        }
-    };
-
-    // ---- staging: wave wv issues transfer instructions wv, wv+4, ... of each operand; instruction q
+    // ---- staging.  Wave wv issues transfer instructions wv, wv+4, ... of each operand; instruction q
     // carries tile rows RPI*q .. RPI*q+RPI-1.  A row beyond the context re-loads the last row, a missing
     // column re-loads row 0: every slot is always written with finite data and needs no exec masking.
+    // (Measured: spreading the transfers over the products of the previous tile instead of issuing
+    // them together is slower; a transfer stalls the wave that issues it for as long as the vector
+    // memory pipeline is busy, which then also stalls its matrix pipeline.)
     auto issue = [&](int t) {                              // global -> LDS buffer t & 1 for tile t
         const uint32_t dst = tiles_lds + (uint32_t)((t & 1) * C::TILE_BYTES);
         const uint32_t kdst = dst + (uint32_t)(wv * C::K_ISTR), vdst = dst + (uint32_t)(C::K_BYTES + wv * C::V_ISTR);
@@ -898,34 +797,129 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
             }
         }
     };
-    // column ids of gathered tile t: fetched into a register one iteration before they are written to
-    // LDS (slot t % 3), which happens one iteration before tile t is issued.  The global load is thus
-    // never waited for while transfers are in flight.
-    auto fetch_cols = [&](int t) -> int32_t {
-        if (t >= n1 && t < ntiles && tid < BN) {
-            const int idx = (t - n1) * BN + tid;
-            return idx < nv ? vi[idx] : -1;
+
+    // One tile: S^T = K Q^T, online softmax, O^T += V^T P^T.  The products run in a pinned order
+    // (a scheduling barrier after each) with the LDS fragment reads a fixed number of products ahead.
+    auto process = [&](int tileoff, uint32_t am0, uint32_t am1, bool full) {
+        const unsigned char* tile = tiles + tileoff;
+        f32x16 s[2];
+        bool act[2];
+        act[0] = __ballot(am0 != 0u) != 0ull;
+        act[1] = __ballot(am1 != 0u) != 0ull;
+        if (!act[0] && !act[1]) return;                    // none of this wave's rows has an allowed cell here
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[0] = zero16; s[1] = zero16;
+        constexpr int SUB = (32 / C::RPI) * C::K_ISTR;     // LDS bytes from key r to key r + 32
+        const bool both = act[0] && act[1];
+        if (both) {
+            // 2 * KSTEPS products in a fixed order; K fragments are read RING_S products ahead of their use
+            constexpr int NP = 2 * C::KSTEPS, R = LS_RING_S;
+            Frag<T> kf[NP];
+            auto kload = [&](int i) {
+                const int c = i >> 1;
+                load_frag(kf[i], tile + kaddr[c & (C::KA - 1)] + (i & 1) * SUB + 32 * (c & ~(C::KA - 1)));
+            };
+#pragma unroll
+            for (int i = 0; i < R; ++i) kload(i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                mma(s[i & 1], kf[i], qf[i >> 1]);          // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
+                if (i + R < NP) kload(i + R);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                if (!act[sub]) continue;
+#pragma unroll
+                for (int c = 0; c < C::KSTEPS; ++c) {
+                    Frag<T> kf;
+                    load_frag(kf, tile + kaddr[c & (C::KA - 1)] + sub * SUB + 32 * (c & ~(C::KA - 1)));
+                    mma(s[sub], kf, qf[c]);
+                }
+            }
         }
-        return -1;
-    };
-    auto store_cols = [&](int t, int32_t c) {
-        if (t >= n1 && t < ntiles && tid < BN) colring[(t % 3) * BN + tid] = c;
+        float mx = -INFINITY;
+        if (full) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const uint32_t amg = (sub ? am1 : am0) >> (4 * g);   // register r of this lane: key 8(r/4) + 4g + r%4
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float x = (amg & (1u << (8 * (r >> 2) + (r & 3)))) ? s[sub][r] : -INFINITY;
+                    s[sub][r] = x;
+                    mx = fmaxf(mx, x);
+                }
+            }
+        }
+        mx = fmaxf(mx, xor32(mx));
+        const float m_new = (mx > m_run + lazy) ? mx : m_run;            // -inf + lazy = -inf: the first finite tile always moves it
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = fast_exp2((m_run - m_safe) * sc2);
+        const float mneg = -m_safe * sc2;
+        m_run = m_new;
+        float ps4[4] = {0.f, 0.f, 0.f, 0.f};               // four short add chains instead of one long one
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(__builtin_fmaf(s[sub][r], sc2, mneg));
+                s[sub][r] = p;
+                ps4[r & 3] += p;
+            }
+        l_run = l_run * corr + ((ps4[0] + ps4[1]) + (ps4[2] + ps4[3]));
+        if (__ballot(corr != 1.0f) != 0ull) {
+#pragma unroll
+            for (int i = 0; i < C::DBLK; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+        }
+        auto vt_frag = [&](Frag<T>& vf, int q4, int i) {     // V^T fragment: keys 16*q4.., output block i
+            const unsigned char* va = tile + vaddr[i] + 16 * q4 * C::RB;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * C::RB));
+            struct U { s16x4 a, b; } u = {lo, hi};
+            vf.v = __builtin_bit_cast(bf16x8, u);
+        };
+        // P*V: per 32-key half, 2 * DBLK products in a fixed order (16-key chunk q4, output block i); V^T
+        // fragments are read RING_P products ahead
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            if (act[sub]) {
+                constexpr int NPV = 2 * C::DBLK, R = LS_RING_P < NPV ? LS_RING_P : NPV;
+                Frag<T> pf[2];
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    float pv[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pv[e] = s[sub][8 * h2 + e];
+                    pack_frag(pf[h2], pv);
+                }
+                Frag<T> vf[NPV];
+#pragma unroll
+                for (int k = 0; k < R; ++k) vt_frag(vf[k], 2 * sub + k / C::DBLK, k % C::DBLK);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k = 0; k < NPV; ++k) {
+                    mma(oacc[k % C::DBLK], vf[k], pf[k / C::DBLK]);
+                    if (k + R < NPV) vt_frag(vf[k + R], 2 * sub + (k + R) / C::DBLK, (k + R) % C::DBLK);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
     };
 
-    store_cols(0, fetch_cols(0));
-    store_cols(1, fetch_cols(1));
-    int32_t colpre = fetch_cols(2);
-    __syncthreads();                                       // bitmap, table, kbl, first column ids visible
-    if (ntiles > 0) issue(0);
-    wait_transfers();
-    __syncthreads();
-
-    for (int t = 0; t < ntiles; ++t) {
-        store_cols(t + 2, colpre);
-        colpre = fetch_cols(t + 3);
-        if (t + 1 < ntiles) issue(t + 1);
-        uint32_t am0 = 0u, am1 = 0u;
-        bool full = false;
+    // cell masks of tile t for this lane's row: bit j of am0 / am1 = key j / 32 + j of the tile is allowed
+    uint32_t am0 = 0u, am1 = 0u;
+    bool full = false;
+    auto masks = [&](int t) {
+        am0 = 0u; am1 = 0u; full = false;
         if (t < n1) {
             const int e = __builtin_amdgcn_readfirstlane((int)kbl[t]);
             const int64_t key0 = (int64_t)(e & 0x3FFF) * BN;
@@ -961,7 +955,36 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
             }
             am0 = (uint32_t)am; am1 = (uint32_t)(am >> 32);
         }
+    };
+
+    // column ids of gathered tile t: fetched into a register one iteration before they are written to
+    // LDS (slot t % 3), which happens one iteration before tile t is issued.  The global load is thus
+    // never waited for while transfers are in flight.
+    auto fetch_cols = [&](int t) -> int32_t {
+        if (t >= n1 && t < ntiles && tid < BN) {
+            const int idx = (t - n1) * BN + tid;
+            return idx < nv ? vi[idx] : -1;
+        }
+        return -1;
+    };
+    auto store_cols = [&](int t, int32_t c) {
+        if (t >= n1 && t < ntiles && tid < BN) colring[(t % 3) * BN + tid] = c;
+    };
+
+    store_cols(0, fetch_cols(0));
+    store_cols(1, fetch_cols(1));
+    int32_t colpre = fetch_cols(2);
+    __syncthreads();                                       // bitmap, table, kbl, first column ids visible
+    if (ntiles > 0) { issue(0); masks(0); }
+    wait_transfers();
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        store_cols(t + 2, colpre);
+        colpre = fetch_cols(t + 3);
+        if (t + 1 < ntiles) issue(t + 1);
         process((t & 1) * C::TILE_BYTES, am0, am1, full);
+        if (t + 1 < ntiles) masks(t + 1);                  // its LDS reads overlap the wait below
         wait_transfers();                                  // this wave's transfers of tile t+1 have landed
         __syncthreads();
     }
