@@ -21,6 +21,7 @@
 //
 // Tile products: S^T = K_tile * Q^T and O^T += V_tile^T * P^T on 32x32 MFMA, fp32 accumulation,
 // online softmax in the base-2 domain.  K is staged row-major in LDS, V transposed (see vt_col).
+#include <type_traits>
 #include "ls_device.h"
 #include "ls_internal.h"
 
@@ -829,16 +830,23 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
+            // one 32-key half: KSTEPS products on one accumulator, same ring
+            auto half = [&](auto subc) {
+                constexpr int sub = decltype(subc)::value;
+                constexpr int R = LS_RING_S < C::KSTEPS ? LS_RING_S : C::KSTEPS;
+                Frag<T> kf[C::KSTEPS];
+                auto kload = [&](int c) { load_frag(kf[c], tile + kaddr[c & (C::KA - 1)] + sub * SUB + 32 * (c & ~(C::KA - 1))); };
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                if (!act[sub]) continue;
+                for (int c = 0; c < R; ++c) kload(c);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int c = 0; c < C::KSTEPS; ++c) {
-                    Frag<T> kf;
-                    load_frag(kf, tile + kaddr[c & (C::KA - 1)] + sub * SUB + 32 * (c & ~(C::KA - 1)));
-                    mma(s[sub], kf, qf[c]);
+                    mma(s[sub], kf[c], qf[c]);
+                    if (c + R < C::KSTEPS) kload(c + R);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            }
+            };
+            if (act[0]) half(std::integral_constant<int, 0>{}); else half(std::integral_constant<int, 1>{});
         }
         float mx = -INFINITY;
         if (full) {

@@ -142,11 +142,15 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_kernel(SelectArgs a) {
 constexpr int WALK_THREADS = 64;
 constexpr int WALK_WIN = 2048;                 // window of each list kept in LDS
 constexpr int WALK_LOOK = 64;                  // lookahead the run evaluation needs
+constexpr size_t WALK_LDS_BYTES = (6 * WALK_WIN + 2 * (WALK_WIN + 4)) * sizeof(float);
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
 __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
-    __shared__ float cw[2][WALK_WIN], cl[2][WALK_WIN], cm[2][WALK_WIN];
-    __shared__ float pre[2][WALK_WIN + 1];     // pre[l][i]: overlap sum when base_l + i lines of list l are taken
+    extern __shared__ __align__(16) float walk_lds[];       // WALK_LDS_BYTES
+    float (*cw)[WALK_WIN] = reinterpret_cast<float (*)[WALK_WIN]>(walk_lds);
+    float (*cl)[WALK_WIN] = cw + 2;
+    float (*cm)[WALK_WIN] = cw + 4;
+    float (*pre)[WALK_WIN + 4] = reinterpret_cast<float (*)[WALK_WIN + 4]>(walk_lds + 6 * WALK_WIN);   // pre[l][i]: overlap sum when base_l + i lines of list l are taken
     const int bh = blockIdx.x, lane = threadIdx.x;
     const int n = (int)a.n;
     const int64_t nh = a.n_hat;
@@ -169,24 +173,51 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         for (int l = 0; l < 2; ++l) {
             if (!need[l]) continue;
             base[l] = head[l];
-            for (int i = lane; i < WALK_WIN; i += WALK_THREADS) {
-                const int gi = base[l] + i;
-                float w = 0.f, m = 0.f, len = 1.f;
-                if (gi < n) {
-                    const int64_t x = i_l[l][gi];
-                    w = w_l[l][gi]; m = m_l[l][gi];
-                    len = (float)((a.n - x) < nh ? (a.n - x) : nh);       // line length in the n_hat x n block
-                }
-                cw[l][i] = w; cm[l][i] = m; cl[l][i] = len;
+            // all loads of the window first (they are independent), then the LDS stores
+            constexpr int PER = WALK_WIN / WALK_THREADS;
+            float fw[PER], fm[PER]; int32_t fx[PER];
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const int gi = base[l] + lane + j * WALK_THREADS;
+                const int gc = gi < n ? gi : n - 1;
+                fx[j] = i_l[l][gc]; fw[j] = w_l[l][gc]; fm[j] = m_l[l][gc];
+            }
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const int i = lane + j * WALK_THREADS;
+                const bool in = base[l] + i < n;
+                const int64_t x = fx[j];
+                cw[l][i] = in ? fw[j] : 0.f;
+                cm[l][i] = in ? fm[j] : 0.f;
+                cl[l][i] = in ? (float)((a.n - x) < nh ? (a.n - x) : nh) : 1.f;   // line length in the n_hat x n block
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
         if (lane < 2 && (lane == 0 ? need[0] : need[1])) {
+            // one add after the other, in list order; the next 16 maxima are read while the current 16 are added
             float acc = lane == 0 ? carry[0] : carry[1];
-            const float* src = cm[lane];
+            const f32x4* src = reinterpret_cast<const f32x4*>(cm[lane]);
             float* dst = pre[lane];
-            for (int i = 0; i < WALK_WIN; ++i) { dst[i] = acc; acc = __fadd_rn(acc, src[i]); }
+            f32x4 cur[4], nxt[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) cur[q] = src[q];
+            for (int i = 0; i < WALK_WIN; i += 16) {
+                const int ni = i + 16 < WALK_WIN ? i + 16 : i;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) nxt[q] = src[ni / 4 + q];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 o;
+                    o.x = acc; acc = __fadd_rn(acc, cur[q].x);
+                    o.y = acc; acc = __fadd_rn(acc, cur[q].y);
+                    o.z = acc; acc = __fadd_rn(acc, cur[q].z);
+                    o.w = acc; acc = __fadd_rn(acc, cur[q].w);
+                    *reinterpret_cast<f32x4*>(dst + i + 4 * q) = o;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+            }
             dst[WALK_WIN] = acc;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -250,7 +281,17 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             const int gbits = __builtin_bit_cast(int, gain);
             int taken = 0;
             bool reached = false;
-            while (taken + 8 <= limit) {
+            // Every applied gain is positive when the walk stops at the first non-positive head (see `dead`),
+            // so the partial sums do not decrease: a group of 16 can be added with one test of its last sum.
+            while (early && taken + 16 <= limit) {
+                float acc = sum;
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    acc = __fadd_rn(acc, __builtin_bit_cast(float, __builtin_amdgcn_readlane(gbits, taken + u)));
+                if (!(acc < target)) break;                // the target falls inside this group: add it pick by pick below
+                sum = acc; taken += 16;
+            }
+            while (!early && taken + 8 <= limit) {
                 float ps[8];
                 float acc = sum;
 #pragma unroll
@@ -413,9 +454,12 @@ __global__ void gather_rows_kernel(const unsigned char* src, unsigned char* dst,
 
 hipError_t run_select(const SelectArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(sort_kernel, dim3(2, a.BH), dim3(SORT_THREADS), 0, st, a);
-    hipLaunchKernelGGL(walk_kernel, dim3(a.BH), dim3(WALK_THREADS), 0, st, a);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&walk_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)WALK_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(walk_kernel, dim3(a.BH), dim3(WALK_THREADS), WALK_LDS_BYTES, st, a);
     const size_t smem = (size_t)((a.n + 31) / 32) * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&emit_kernel),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&emit_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(emit_kernel, dim3(2, a.BH), dim3(1024), smem, st, a);
