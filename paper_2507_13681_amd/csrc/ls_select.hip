@@ -1,11 +1,14 @@
 // Per-head line selection (Alg. 2 from Desc_Sort on) and top-B retention (Alg. 3), gfx950.
 //
-//   sort_kernel   one workgroup per (head, list): stable LSD radix sort (4 x 8 bits) of the n line
-//                 weights in descending order; equal weights keep ascending index order.  Each of
-//                 the 16 waves owns a contiguous slice of the input, counts its digits in its own
-//                 LDS histogram, and scatters its slice in order: inside a 64-element chunk the
-//                 rank among equal digits comes from wave ballots, across chunks from the wave's
-//                 running counters.  No atomics decide an output position.
+//   sort_seg_kernel / sort_merge_kernel
+//                 Desc_Sort: the n line weights of a list in descending order, equal weights in
+//                 ascending index order.  Segments of 8192 elements are sorted inside LDS by a stable
+//                 LSD radix sort (4 x 8 bits): each of the 16 waves owns a contiguous slice, counts its
+//                 digits in its own histogram, and scatters its slice in order (ranks among equal
+//                 digits from wave ballots and the wave's running counters; no atomics decide an
+//                 output position).  The sorted segments are then merged by rank: every element's
+//                 final position is its position in its segment plus, by bisection, the number of
+//                 elements of the other segments that precede it.
 //   walk_kernel   one wave per head: the greedy loop of Alg. 2 in binary32 with the operands and
 //                 operation order of the definition; runs of picks from one list are decided 64 at a
 //                 time by the lanes, the running sum is accumulated pick by pick.
@@ -32,34 +35,44 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {
 
 constexpr int SORT_THREADS = 1024;
 constexpr int SORT_WAVES = 16;
+constexpr int SORT_SEG = 8192;                 // elements one workgroup sorts inside LDS
+constexpr int SORT_SLICE = SORT_SEG / SORT_WAVES;
+constexpr size_t SORT_LDS_BYTES = 2 * SORT_SEG * 4 + 2 * SORT_SEG * 2 + SORT_WAVES * 256 * 4 + 256 * 4;
 
-// grid (2, BH): list 0 = diagonals (slash), 1 = columns (vert).
-__global__ __launch_bounds__(SORT_THREADS) void sort_kernel(SelectArgs a) {
-    __shared__ uint32_t hist[SORT_WAVES][256];
-    __shared__ uint32_t dbase[256];
-    const int list = blockIdx.x, bh = blockIdx.y;
+// grid (segments, 2, BH): list 0 = diagonals (slash), 1 = columns (vert).  Sorts elements
+// [seg * SORT_SEG, +SORT_SEG) of one list entirely in LDS and writes the sorted keys (skey0) and their
+// line indices (sidx0) back to the same range.
+__global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
+    extern __shared__ __align__(16) unsigned char sort_lds[];
+    uint32_t* kb0 = reinterpret_cast<uint32_t*>(sort_lds);
+    uint32_t* kb1 = kb0 + SORT_SEG;
+    uint16_t* ib0 = reinterpret_cast<uint16_t*>(kb1 + SORT_SEG);
+    uint16_t* ib1 = ib0 + SORT_SEG;
+    uint32_t (*hist)[256] = reinterpret_cast<uint32_t (*)[256]>(ib1 + SORT_SEG);
+    uint32_t* dbase = &hist[SORT_WAVES][0];
+    const int seg = blockIdx.x, list = blockIdx.y, bh = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t n = a.n;
-    const float* src = (list == 0 ? a.slash : a.vert) + (int64_t)bh * n;
-    const int64_t seg = ((int64_t)list * a.BH + bh) * n;
-    uint32_t* kbuf[2] = {a.skey0 + seg, a.skey1 + seg};
-    int32_t* ibuf[2] = {a.sidx0 + seg, a.sidx1 + seg};
-    const int64_t slice = (((n + SORT_WAVES - 1) / SORT_WAVES) + 63) / 64 * 64;
-    const int64_t lo = (int64_t)wv * slice;
-    const int64_t hi = lo + slice < n ? lo + slice : n;
-
+    const int64_t base0 = (int64_t)seg * SORT_SEG;
+    const int cnt = (int)(n - base0 < SORT_SEG ? n - base0 : SORT_SEG);
+    const float* src = (list == 0 ? a.slash : a.vert) + (int64_t)bh * n + base0;
+    const int64_t out0 = ((int64_t)list * a.BH + bh) * n + base0;
+    // slots past the end of the list hold the largest key: they sort behind every element and, being
+    // the highest local indices, stay behind equal keys as well
+    for (int i = tid; i < SORT_SEG; i += SORT_THREADS) {
+        kb0[i] = i < cnt ? desc_key(src[i]) : 0xFFFFFFFFu;
+        ib0[i] = (uint16_t)i;
+    }
+    const int lo = wv * SORT_SLICE;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 8 * pass;
-        const uint32_t* kin = kbuf[(pass + 1) & 1];        // pass 0 reads src directly
-        const int32_t* iin = ibuf[(pass + 1) & 1];
-        uint32_t* kout = kbuf[pass & 1];
-        int32_t* iout = ibuf[pass & 1];
+        const uint32_t* kin = (pass & 1) ? kb1 : kb0;
+        const uint16_t* iin = (pass & 1) ? ib1 : ib0;
+        uint32_t* kout = (pass & 1) ? kb0 : kb1;
+        uint16_t* iout = (pass & 1) ? ib0 : ib1;
         for (int i = tid; i < SORT_WAVES * 256; i += SORT_THREADS) (&hist[0][0])[i] = 0u;
         __syncthreads();
-        for (int64_t i = lo + lane; i < hi; i += 64) {
-            const uint32_t key = pass == 0 ? desc_key(src[i]) : kin[i];
-            atomicAdd(&hist[wv][(key >> shift) & 255u], 1u);
-        }
+        for (int i = lo + lane; i < lo + SORT_SLICE; i += 64) atomicAdd(&hist[wv][(kin[i] >> shift) & 255u], 1u);
         __syncthreads();
         // exclusive offsets in (digit, wave) order
         if (tid < 256) {
@@ -69,13 +82,13 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_kernel(SelectArgs a) {
         }
         __syncthreads();
         if (tid < 64) {                                    // scan of 256 digit totals by one wave
-            uint32_t v[4], s = 0;
+            uint32_t v[4], sm = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) { v[q] = dbase[4 * tid + q]; s += v[q]; }
-            uint32_t inc = s;
+            for (int q = 0; q < 4; ++q) { v[q] = dbase[4 * tid + q]; sm += v[q]; }
+            uint32_t inc = sm;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
-            uint32_t ex = inc - s;
+            uint32_t ex = inc - sm;
 #pragma unroll
             for (int q = 0; q < 4; ++q) { dbase[4 * tid + q] = ex; ex += v[q]; }
         }
@@ -85,45 +98,89 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_kernel(SelectArgs a) {
             for (int w = 0; w < SORT_WAVES; ++w) hist[w][tid] += bs;
         }
         __syncthreads();
-        // in-order scatter of this wave's slice
+        // in-order scatter of this wave's slice: inside a 64-element chunk the rank among equal digits
+        // comes from wave ballots, across chunks from the wave's running counters
         volatile uint32_t* myh = hist[wv];
-        for (int64_t c0 = lo; c0 < hi; c0 += 64) {
-            const int64_t i = c0 + lane;
-            const bool ok = i < hi;
-            uint32_t key = 0; int32_t idx = 0;
-            if (ok) { key = pass == 0 ? desc_key(src[i]) : kin[i]; idx = pass == 0 ? (int32_t)i : iin[i]; }
+#pragma unroll
+        for (int c = 0; c < SORT_SLICE / 64; ++c) {
+            const int i = lo + 64 * c + lane;
+            const uint32_t key = kin[i];
+            const uint16_t idx = iin[i];
             const uint32_t dg = (key >> shift) & 255u;
-            uint64_t peers = __ballot(ok);
+            uint64_t peers = ~0ull;
 #pragma unroll
             for (int bit = 0; bit < 8; ++bit) {
                 const bool one = (dg >> bit) & 1u;
-                const uint64_t bal = __ballot(ok && one);
+                const uint64_t bal = __ballot(one);
                 peers &= one ? bal : ~bal;
             }
             const uint64_t below = peers & ((1ull << lane) - 1ull);
             const uint32_t rank = __popcll(below);
-            uint32_t base = 0;
-            if (ok) base = myh[dg];
+            const uint32_t pos = myh[dg] + rank;
             __builtin_amdgcn_wave_barrier();
-            if (ok) {
-                kout[base + rank] = key;
-                iout[base + rank] = idx;
-                if (below == 0ull) myh[dg] = base + (uint32_t)__popcll(peers);
-            }
+            kout[pos] = key;
+            iout[pos] = idx;
+            if (below == 0ull) myh[dg] = pos + (uint32_t)__popcll(peers);
             __builtin_amdgcn_wave_barrier();
         }
-        __threadfence_block();
-        __syncthreads();
+        __syncthreads();                                   // every wave is done with the counters and the input buffer
     }
-    // after 4 passes the result sits in buffer 1 ((3 & 1) = 1); attach weight and the line's largest entry
-    const uint32_t* kfin = kbuf[1];
-    const int32_t* ifin = ibuf[1];
+    // four passes: the result sits in buffer 0
+    for (int i = tid; i < cnt; i += SORT_THREADS) {
+        a.skey0[out0 + i] = kb0[i];
+        a.sidx0[out0 + i] = (int32_t)(base0 + ib0[i]);
+    }
+}
+
+// grid (segments, 2, BH).  Final position of an element of segment q = its position inside q + the
+// number of elements of every other segment that go before it: smaller key, or equal key in a segment
+// of smaller line indices (the order stays stable).  The other segments' sorted keys are staged in
+// LDS one at a time and searched by bisection.  Writes the sorted weights, line indices (sidx1) and
+// each line's largest entry.
+constexpr int MERGE_PER = SORT_SEG / SORT_THREADS;
+__global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) {
+    __shared__ uint32_t other[SORT_SEG];
+    const int seg = blockIdx.x, list = blockIdx.y, bh = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int64_t n = a.n;
+    const int nseg = (int)((n + SORT_SEG - 1) / SORT_SEG);
+    const int64_t lbase = ((int64_t)list * a.BH + bh) * n;
+    const int64_t base0 = (int64_t)seg * SORT_SEG;
+    const int cnt = (int)(n - base0 < SORT_SEG ? n - base0 : SORT_SEG);
+    uint32_t key[MERGE_PER]; uint32_t rank[MERGE_PER];
+#pragma unroll
+    for (int j = 0; j < MERGE_PER; ++j) {
+        const int p = tid + j * SORT_THREADS;
+        key[j] = p < cnt ? a.skey0[lbase + base0 + p] : 0xFFFFFFFFu;
+        rank[j] = (uint32_t)p;
+    }
+    for (int q = 0; q < nseg; ++q) {
+        if (q == seg) continue;
+        const int64_t qb = (int64_t)q * SORT_SEG;
+        const int qc = (int)(n - qb < SORT_SEG ? n - qb : SORT_SEG);
+        __syncthreads();
+        for (int i = tid; i < SORT_SEG; i += SORT_THREADS) other[i] = i < qc ? a.skey0[lbase + qb + i] : 0xFFFFFFFFu;
+        __syncthreads();
+        const uint32_t incl = q < seg ? 1u : 0u;           // equal keys of an earlier segment go first
+#pragma unroll
+        for (int j = 0; j < MERGE_PER; ++j) {
+            // number of i in [0, qc) with other[i] < key + incl (as 64-bit: key may be 0xFFFFFFFF)
+            const uint64_t lim = (uint64_t)key[j] + incl;
+            int lo = 0, hi = qc;
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if ((uint64_t)other[mid] < lim) lo = mid + 1; else hi = mid; }
+            rank[j] += (uint32_t)lo;
+        }
+    }
     const float* mx = (list == 0 ? a.smax : a.vmax) + (int64_t)bh * n;
-    float* ow = a.sorted_w + seg;
-    float* om = a.sorted_m + seg;
-    for (int64_t i = tid; i < n; i += SORT_THREADS) {
-        ow[i] = key_to_float(kfin[i]);
-        om[i] = mx[ifin[i]];
+#pragma unroll
+    for (int j = 0; j < MERGE_PER; ++j) {
+        const int p = tid + j * SORT_THREADS;
+        if (p < cnt) {
+            const int32_t idx = a.sidx0[lbase + base0 + p];
+            a.sorted_w[lbase + rank[j]] = key_to_float(key[j]);
+            a.sidx1[lbase + rank[j]] = idx;
+            a.sorted_m[lbase + rank[j]] = mx[idx];
+        }
     }
 }
 
@@ -453,8 +510,13 @@ __global__ void gather_rows_kernel(const unsigned char* src, unsigned char* dst,
 }
 
 hipError_t run_select(const SelectArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(sort_kernel, dim3(2, a.BH), dim3(SORT_THREADS), 0, st, a);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&walk_kernel),
+    const int nseg = (int)((a.n + SORT_SEG - 1) / SORT_SEG);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sort_seg_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)SORT_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sort_seg_kernel, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), SORT_LDS_BYTES, st, a);
+    hipLaunchKernelGGL(sort_merge_kernel, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), 0, st, a);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&walk_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)WALK_LDS_BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(walk_kernel, dim3(a.BH), dim3(WALK_THREADS), WALK_LDS_BYTES, st, a);
