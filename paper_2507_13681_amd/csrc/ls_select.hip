@@ -9,9 +9,10 @@
 //                 output position).  The sorted segments are then merged by rank: every element's
 //                 final position is its position in its segment plus, by bisection, the number of
 //                 elements of the other segments that precede it.
-//   walk_kernel   one wave per head: the greedy loop of Alg. 2 in binary32 with the operands and
+//   walk_kernel   one walking wave per head: the greedy loop of Alg. 2 in binary32 with the operands and
 //                 operation order of the definition; runs of picks from one list are decided 64 at a
-//                 time by the lanes, the running sum is accumulated pick by pick.
+//                 time by the lanes, the running sum is accumulated pick by pick.  A second wave
+//                 stages the sorted lists and their overlap prefix sums in LDS ahead of the walk.
 //   emit_kernel   one workgroup per (head, list): the chosen prefix of a sorted list becomes an
 //                 ascending index list (bitmap in LDS + prefix popcount).
 //   topb_kernel   Alg. 3: the `budget` largest scores per KV head by 4-pass radix select on the
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 }
 
 // ---- the greedy loop ----------------------------------------------------------------------------
-// One wave per head.  The loop of Alg. 2 is sequential, but two things about it are not:
+// One workgroup of two waves per head.  The loop of Alg. 2 is sequential, but two things about it are not:
 //   * ol_s after k slashes were taken is the left-to-right binary32 sum of the first k maxima of
 //     the slash list, whatever the interleaving with verticals was (likewise ol_v), so both
 //     running overlaps are prefix arrays that can be filled ahead of the walk (still added one
@@ -196,191 +197,237 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 // What stays sequential is the accumulation of `sum` with its exit test after every pick: one
 // add and one compare per pick, on values already sitting in the lanes' registers.
 // Each pick therefore sees exactly the operands, operation order and roundings of the definition.
-constexpr int WALK_THREADS = 64;
-constexpr int WALK_WIN = 2048;                 // window of each list kept in LDS
-constexpr int WALK_LOOK = 64;                  // lookahead the run evaluation needs
-constexpr size_t WALK_LDS_BYTES = (6 * WALK_WIN + 2 * (WALK_WIN + 4)) * sizeof(float);
+constexpr int WALK_THREADS = 128;              // wave 0 walks; wave 1 fills the list windows ahead of it
+constexpr int WALK_WIN = 1024;                 // window of a list kept in LDS
+constexpr int WALK_STRIDE = WALK_WIN - 128;    // window k of a list covers sorted positions [k * STRIDE, k * STRIDE + WIN)
+constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the two waves (never reached; about a second)
+
+// One window of one sorted list: weights, line lengths, largest entries, and pre[i] = the overlap sum
+// when the first k * STRIDE + i lines of the list have been taken.
+struct WalkWin { float cw[WALK_WIN], cl[WALK_WIN], cm[WALK_WIN], pre[WALK_WIN + 4]; };
+struct WalkSync { int ready[2], cur[2], done, err, pad[2]; };
+constexpr size_t WALK_LDS_BYTES = 4 * sizeof(WalkWin) + sizeof(WalkSync);
+
+__device__ __forceinline__ int walk_ld(const int* p) { return __builtin_amdgcn_readfirstlane(__atomic_load_n(p, __ATOMIC_RELAXED)); }
+__device__ __forceinline__ void walk_st(int* p, int v) { __atomic_store_n(p, v, __ATOMIC_RELAXED); }
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
+//
+// The two waves share only LDS.  Wave 1 keeps two consecutive windows of each list resident
+// (window k goes to buffer k & 1): it produces window k of list l as soon as the walker's current
+// window of that list is >= k - 1, then publishes ready[l] = k + 1.  The walker publishes cur[l]
+// when it moves on to the next window, which frees the buffer of the one before.  Every wait is a
+// bounded spin; the walker ends both loops through `done`.
 __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
-    extern __shared__ __align__(16) float walk_lds[];       // WALK_LDS_BYTES
-    float (*cw)[WALK_WIN] = reinterpret_cast<float (*)[WALK_WIN]>(walk_lds);
-    float (*cl)[WALK_WIN] = cw + 2;
-    float (*cm)[WALK_WIN] = cw + 4;
-    float (*pre)[WALK_WIN + 4] = reinterpret_cast<float (*)[WALK_WIN + 4]>(walk_lds + 6 * WALK_WIN);   // pre[l][i]: overlap sum when base_l + i lines of list l are taken
-    const int bh = blockIdx.x, lane = threadIdx.x;
+    extern __shared__ __align__(16) unsigned char walk_lds[];
+    WalkWin (*win)[2] = reinterpret_cast<WalkWin (*)[2]>(walk_lds);          // [list][buffer]
+    WalkSync* sync = reinterpret_cast<WalkSync*>(walk_lds + 4 * sizeof(WalkWin));
+    const int bh = blockIdx.x, lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = (int)a.n;
     const int64_t nh = a.n_hat;
     const int64_t seg_s = ((int64_t)0 * a.BH + bh) * a.n, seg_v = ((int64_t)1 * a.BH + bh) * a.n;
-    const float* w_l[2] = {a.sorted_w + seg_s, a.sorted_w + seg_v};
-    const float* m_l[2] = {a.sorted_m + seg_s, a.sorted_m + seg_v};
-    const int32_t* i_l[2] = {a.sidx1 + seg_s, a.sidx1 + seg_v};
+
+    if (threadIdx.x == 0) { sync->ready[0] = sync->ready[1] = 0; sync->cur[0] = sync->cur[1] = 0; sync->done = 0; sync->err = 0; }
+    __syncthreads();
+
+    if (wv == 1) {
+        // ------------------------------------------------------------------ window producer
+        const float* w_l[2] = {a.sorted_w + seg_s, a.sorted_w + seg_v};
+        const float* m_l[2] = {a.sorted_m + seg_s, a.sorted_m + seg_v};
+        const int32_t* i_l[2] = {a.sidx1 + seg_s, a.sidx1 + seg_v};
+        float carry[2] = {0.f, 0.f};           // overlap sum at the start of the next window of each list
+        int produced[2] = {0, 0};
+        int spins = 0;
+        while (walk_ld(&sync->done) == 0) {
+            bool need[2];
+#pragma unroll
+            for (int l = 0; l < 2; ++l)
+                need[l] = produced[l] < walk_ld(&sync->cur[l]) + 2 && (int64_t)produced[l] * WALK_STRIDE < n;
+            if (!need[0] && !need[1]) {
+                __builtin_amdgcn_s_sleep(2);
+                if (++spins > WALK_SPIN_LIMIT) { walk_st(&sync->err, 1); break; }
+                continue;
+            }
+            spins = 0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+            for (int l = 0; l < 2; ++l) {
+                if (!need[l]) continue;
+                WalkWin& W = win[l][produced[l] & 1];
+                const int base = produced[l] * WALK_STRIDE;
+                // all loads of the window first (they are independent), then the LDS stores
+                constexpr int PER = WALK_WIN / 64;
+                float fw[PER], fm[PER]; int32_t fx[PER];
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    const int gi = base + lane + j * 64;
+                    const int gc = gi < n ? gi : n - 1;
+                    fx[j] = i_l[l][gc]; fw[j] = w_l[l][gc]; fm[j] = m_l[l][gc];
+                }
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    const int i = lane + j * 64;
+                    const bool in = base + i < n;
+                    const int64_t x = fx[j];
+                    W.cw[i] = in ? fw[j] : 0.f;
+                    W.cm[i] = in ? fm[j] : 0.f;
+                    W.cl[i] = in ? (float)((a.n - x) < nh ? (a.n - x) : nh) : 1.f;   // line length in the n_hat x n block
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            float next_carry = 0.f;
+            if (lane < 2 && (lane == 0 ? need[0] : need[1])) {
+                // lane l scans list l: one add after the other, in list order; the next 16 maxima are read
+                // while the current 16 are added
+                WalkWin& W = win[lane][(lane == 0 ? produced[0] : produced[1]) & 1];
+                float acc = lane == 0 ? carry[0] : carry[1];
+                const f32x4* src = reinterpret_cast<const f32x4*>(W.cm);
+                float* dst = W.pre;
+                f32x4 cur[4], nxt[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) cur[q] = src[q];
+                for (int i = 0; i < WALK_WIN; i += 16) {
+                    const int ni = i + 16 < WALK_WIN ? i + 16 : i;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) nxt[q] = src[ni / 4 + q];
+                    if (i == WALK_STRIDE) next_carry = acc;            // STRIDE is a multiple of 16
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 o;
+                        o.x = acc; acc = __fadd_rn(acc, cur[q].x);
+                        o.y = acc; acc = __fadd_rn(acc, cur[q].y);
+                        o.z = acc; acc = __fadd_rn(acc, cur[q].z);
+                        o.w = acc; acc = __fadd_rn(acc, cur[q].w);
+                        *reinterpret_cast<f32x4*>(dst + i + 4 * q) = o;
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+                }
+                dst[WALK_WIN] = acc;
+            }
+            const float c0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, next_carry), 0));
+            const float c1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, next_carry), 1));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            if (need[0]) { carry[0] = c0; ++produced[0]; if (lane == 0) walk_st(&sync->ready[0], produced[0]); }
+            if (need[1]) { carry[1] = c1; ++produced[1]; if (lane == 0) walk_st(&sync->ready[1], produced[1]); }
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- the walk (wave 0)
     const float target = a.alpha * a.total[bh];
     const bool early = a.accounted == nullptr;
-
     int head[2] = {0, 0};                      // is, iv
-    int base[2] = {0, 0};
-    float carry[2] = {0.f, 0.f};               // overlap sums at the window bases
-    bool need[2] = {true, true};
+    int curw[2] = {0, 0};                      // window of each list the heads are in
     float sum = 0.f;
-    bool done = false;
+    bool failed = false;
 
-    while (!done) {
-        // ---- (re)fill the windows that ran low, then their overlap prefixes (lane l scans list l)
-        for (int l = 0; l < 2; ++l) {
-            if (!need[l]) continue;
-            base[l] = head[l];
-            // all loads of the window first (they are independent), then the LDS stores
-            constexpr int PER = WALK_WIN / WALK_THREADS;
-            float fw[PER], fm[PER]; int32_t fx[PER];
-#pragma unroll
-            for (int j = 0; j < PER; ++j) {
-                const int gi = base[l] + lane + j * WALK_THREADS;
-                const int gc = gi < n ? gi : n - 1;
-                fx[j] = i_l[l][gc]; fw[j] = w_l[l][gc]; fm[j] = m_l[l][gc];
-            }
-#pragma unroll
-            for (int j = 0; j < PER; ++j) {
-                const int i = lane + j * WALK_THREADS;
-                const bool in = base[l] + i < n;
-                const int64_t x = fx[j];
-                cw[l][i] = in ? fw[j] : 0.f;
-                cm[l][i] = in ? fm[j] : 0.f;
-                cl[l][i] = in ? (float)((a.n - x) < nh ? (a.n - x) : nh) : 1.f;   // line length in the n_hat x n block
-            }
+    auto wait_ready = [&](int l, int k) {      // until window k of list l is resident
+        int spins = 0;
+        while (walk_ld(&sync->ready[l]) <= k) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
-        if (lane < 2 && (lane == 0 ? need[0] : need[1])) {
-            // one add after the other, in list order; the next 16 maxima are read while the current 16 are added
-            float acc = lane == 0 ? carry[0] : carry[1];
-            const f32x4* src = reinterpret_cast<const f32x4*>(cm[lane]);
-            float* dst = pre[lane];
-            f32x4 cur[4], nxt[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) cur[q] = src[q];
-            for (int i = 0; i < WALK_WIN; i += 16) {
-                const int ni = i + 16 < WALK_WIN ? i + 16 : i;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) nxt[q] = src[ni / 4 + q];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4 o;
-                    o.x = acc; acc = __fadd_rn(acc, cur[q].x);
-                    o.y = acc; acc = __fadd_rn(acc, cur[q].y);
-                    o.z = acc; acc = __fadd_rn(acc, cur[q].z);
-                    o.w = acc; acc = __fadd_rn(acc, cur[q].w);
-                    *reinterpret_cast<f32x4*>(dst + i + 4 * q) = o;
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
-            }
-            dst[WALK_WIN] = acc;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
-        need[0] = need[1] = false;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    };
+    wait_ready(0, 0);
+    wait_ready(1, 0);
 
-        // ---- walk while both heads have WALK_LOOK entries of lookahead inside their windows
-        while (true) {
-            const int is = head[0], iv = head[1];
-            if (!(sum < target) || (is >= n && iv >= n)) { done = true; break; }
-            const bool low_s = is < n && is + WALK_LOOK > base[0] + WALK_WIN && base[0] + WALK_WIN < n;
-            const bool low_v = iv < n && iv + WALK_LOOK > base[1] + WALK_WIN && base[1] + WALK_WIN < n;
-            if (low_s || low_v) {
-                if (low_s) { need[0] = true; carry[0] = pre[0][is - base[0]]; }
-                if (low_v) { need[1] = true; carry[1] = pre[1][iv - base[1]]; }
-                break;
-            }
-            const bool s_has = is < n, v_has = iv < n;
-            // frozen heads of both lists
-            const float ws0 = s_has ? cw[0][is - base[0]] : 0.f, ls0 = s_has ? cl[0][is - base[0]] : 1.f;
-            const float wv0 = v_has ? cw[1][iv - base[1]] : 0.f, lv0 = v_has ? cl[1][iv - base[1]] : 1.f;
-            const float ols0 = pre[0][is - base[0]], olv0 = pre[1][iv - base[1]];
-            // lane j: decision if the walk has taken j more slashes (iv frozen)
-            int i = is + lane;
-            bool ok = i < n && (i - base[0]) < WALK_WIN;
-            int ii = ok ? i - base[0] : 0;
-            float ds = __fsub_rn(cw[0][ii], olv0);
-            float dv = __fsub_rn(wv0, pre[0][ii]);
-            float cs = __fsub_rn(cl[0][ii], (float)iv); if (cs < 1.0f) cs = 1.0f;
-            float cv = __fsub_rn(lv0, (float)i); if (cv < 1.0f) cv = 1.0f;
-            bool take = !v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
-            bool dead = !(ds > 0.f) && (!v_has || !(dv > 0.f));
-            uint64_t bal = __ballot(ok && take);
-            int run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
-            float gain = ds;
-            int which = 0;
-            if (run == 0) {
-                // the head pick is a vertical; lane j: decision if j more verticals are taken (is frozen)
-                which = 1;
-                i = iv + lane;
-                ok = i < n && (i - base[1]) < WALK_WIN;
-                ii = ok ? i - base[1] : 0;
-                dv = __fsub_rn(cw[1][ii], ols0);
-                ds = __fsub_rn(ws0, pre[1][ii]);
-                cv = __fsub_rn(cl[1][ii], (float)is); if (cv < 1.0f) cv = 1.0f;
-                cs = __fsub_rn(ls0, (float)i); if (cs < 1.0f) cs = 1.0f;
-                take = !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
-                dead = !(dv > 0.f) && (!s_has || !(ds > 0.f));
-                bal = __ballot(ok && take);
-                run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
-                gain = dv;
-            }
-            if (run == 0) { done = true; break; }      // cannot happen (lane 0 repeats the head's test); never spin
-            // picks 0 .. run-1 come from list `which`; stop early when no head has a positive gain
-            const uint64_t deadb = __ballot(dead);
-            int stop_dead = 64;
-            if (early && deadb) stop_dead = __ffsll((unsigned long long)deadb) - 1;
-            // picks 0 .. limit-1 are applied; the running sum is accumulated pick by pick (eight adds per
-            // trip, then one test of the eight partial sums against the target)
-            const int limit = run < stop_dead ? run : stop_dead;
-            const int gbits = __builtin_bit_cast(int, gain);
-            int taken = 0;
-            bool reached = false;
-            // Every applied gain is positive when the walk stops at the first non-positive head (see `dead`),
-            // so the partial sums do not decrease: a group of 16 can be added with one test of its last sum.
-            while (early && taken + 16 <= limit) {
-                float acc = sum;
-#pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    acc = __fadd_rn(acc, __builtin_bit_cast(float, __builtin_amdgcn_readlane(gbits, taken + u)));
-                if (!(acc < target)) break;                // the target falls inside this group: add it pick by pick below
-                sum = acc; taken += 16;
-            }
-            while (!early && taken + 8 <= limit) {
-                float ps[8];
-                float acc = sum;
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    acc = __fadd_rn(acc, __builtin_bit_cast(float, __builtin_amdgcn_readlane(gbits, taken + u)));
-                    ps[u] = acc;
-                }
-                int first = 8;
-#pragma unroll
-                for (int u = 7; u >= 0; --u) if (!(ps[u] < target)) first = u;
-                if (first < 8) {
-                    float pick = ps[0];
-#pragma unroll
-                    for (int u = 1; u < 8; ++u) if (first == u) pick = ps[u];
-                    sum = pick; taken += first + 1; reached = true;
-                    break;
-                }
-                sum = acc; taken += 8;
-            }
-            while (!reached && taken < limit) {
-                sum = __fadd_rn(sum, __builtin_bit_cast(float, __builtin_amdgcn_readlane(gbits, taken)));
-                ++taken;
-                if (!(sum < target)) reached = true;
-            }
-            const bool exhausted = !reached && stop_dead < run;      // the pick after the last one has no positive gain
-            head[which] += taken;
-            if (exhausted) { head[0] = n; head[1] = n; done = true; break; }
+    while (!failed) {
+        const int is = head[0], iv = head[1];
+        if (!(sum < target) || (is >= n && iv >= n)) break;
+        // move on to the next window of a list once its head has reached that window's start
+        if (is < n && is >= (curw[0] + 1) * WALK_STRIDE) {
+            ++curw[0];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the window left behind
+            if (lane == 0) walk_st(&sync->cur[0], curw[0]);
+            wait_ready(0, curw[0]);
         }
+        if (iv < n && iv >= (curw[1] + 1) * WALK_STRIDE) {
+            ++curw[1];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) walk_st(&sync->cur[1], curw[1]);
+            wait_ready(1, curw[1]);
+        }
+        if (failed) break;
+        const WalkWin& S = win[0][curw[0] & 1];
+        const WalkWin& V = win[1][curw[1] & 1];
+        const int bs = curw[0] * WALK_STRIDE, bv = curw[1] * WALK_STRIDE;
+        const bool s_has = is < n, v_has = iv < n;
+        const int hs = s_has ? is - bs : 0, hv = v_has ? iv - bv : 0;      // head positions inside the windows
+        // frozen heads of both lists (an exhausted list's overlap sum sits right behind its last line)
+        const float ws0 = s_has ? S.cw[hs] : 0.f, ls0 = s_has ? S.cl[hs] : 1.f;
+        const float wv0 = v_has ? V.cw[hv] : 0.f, lv0 = v_has ? V.cl[hv] : 1.f;
+        const float ols0 = S.pre[is - bs], olv0 = V.pre[iv - bv];
+        // lane j: decision if the walk has taken j more slashes (iv frozen)
+        int i = is + lane;
+        bool ok = i < n && (i - bs) < WALK_WIN;
+        int ii = ok ? i - bs : 0;
+        float ds = __fsub_rn(S.cw[ii], olv0);
+        float dv = __fsub_rn(wv0, S.pre[ii]);
+        float cs = __fsub_rn(S.cl[ii], (float)iv); if (cs < 1.0f) cs = 1.0f;
+        float cv = __fsub_rn(lv0, (float)i); if (cv < 1.0f) cv = 1.0f;
+        bool take = !v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
+        bool dead = !(ds > 0.f) && (!v_has || !(dv > 0.f));
+        uint64_t bal = __ballot(ok && take);
+        int run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
+        float gain = ds;
+        int which = 0;
+        if (run == 0) {
+            // the head pick is a vertical; lane j: decision if j more verticals are taken (is frozen)
+            which = 1;
+            i = iv + lane;
+            ok = i < n && (i - bv) < WALK_WIN;
+            ii = ok ? i - bv : 0;
+            dv = __fsub_rn(V.cw[ii], ols0);
+            ds = __fsub_rn(ws0, V.pre[ii]);
+            cv = __fsub_rn(V.cl[ii], (float)is); if (cv < 1.0f) cv = 1.0f;
+            cs = __fsub_rn(ls0, (float)i); if (cs < 1.0f) cs = 1.0f;
+            take = !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
+            dead = !(dv > 0.f) && (!s_has || !(ds > 0.f));
+            bal = __ballot(ok && take);
+            run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
+            gain = dv;
+        }
+        if (run == 0) break;                   // cannot happen (lane 0 repeats the head's test); never spin
+        // picks 0 .. run-1 come from list `which`; stop early when no head has a positive gain
+        const uint64_t deadb = __ballot(dead);
+        int stop_dead = 64;
+        if (early && deadb) stop_dead = __ffsll((unsigned long long)deadb) - 1;
+        // picks 0 .. limit-1 are applied; the running sum is accumulated pick by pick
+        const int limit = run < stop_dead ? run : stop_dead;
+        // Lane j ends up with the running sum after pick j: x_j = x_{j-1} + gain_j, lane 0 starting from
+        // `sum`.  One pass of "take the left neighbour's value and add my gain" over all lanes settles one
+        // more lane, in order, so `limit` passes reproduce the pick-by-pick additions exactly; the first
+        // lane whose sum reaches the target is the pick the loop of the definition stops after.
+        float x = 0.f;
+        for (int p0 = 0; p0 < limit; p0 += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                    __builtin_bit_cast(int, sum), __builtin_bit_cast(int, x), 0x138 /* wave_shr:1 */, 0xF, 0xF, false));
+                x = __fadd_rn(left, gain);
+            }
+        }
+        const uint64_t lanes = limit >= 64 ? ~0ull : ((1ull << limit) - 1ull);
+        const uint64_t hit = __ballot(!(x < target)) & lanes;
+        int taken = limit;
+        const bool reached = hit != 0ull;
+        if (reached) taken = __ffsll((unsigned long long)hit);          // 1-based position = picks applied
+        if (taken > 0) sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), taken - 1));
+        const bool exhausted = !reached && stop_dead < run;      // the pick after the last one has no positive gain
+        head[which] += taken;
+        if (exhausted) { head[0] = n; head[1] = n; break; }
     }
     if (lane == 0) {
-        a.s_cnt[bh] = head[0];
-        a.v_cnt[bh] = head[1];
+        walk_st(&sync->done, 1);
+        // a wait that ran into its bound (never observed) reports an empty selection
+        a.s_cnt[bh] = failed ? 0 : head[0];
+        a.v_cnt[bh] = failed ? 0 : head[1];
         if (a.accounted) a.accounted[bh] = sum;
     }
 }
