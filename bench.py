@@ -26,7 +26,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/prefill_bf16_kernel_multiturn_32k_counters.md (scaled by the copy-probe factors 2.00 / 1.00).
 # Counters cannot be read inside a timed run, so this is the recorded figure for the default workload only.
-MEASURED_TRAFFIC_BYTES = {("multiturn_32k", 0.95): 2.05e9}
+MEASURED_TRAFFIC_BYTES = {("multiturn_32k", 0.95): 2.33e9}
 
 
 def per_row_cells(n, n_hat, rows_a, v_sel, s_sel):
