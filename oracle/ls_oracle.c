@@ -23,6 +23,9 @@
  *                Sec. 2.2 with M the union of selected columns and diagonals,
  *                restricted to the rows of the newest turn (Sec. 5, Step 1).
  *   lso_compress Alg. 3, the arg-max-B retention formula of Sec. 5.2.
+ *   lso_decode   Alg. 3, the Decoding step: attention of the newest token over the
+ *                retained entries plus every token generated since (the two
+ *                update lines after the step add each new token to the retained set).
  *
  * Readings of points the paper leaves open (each is restated where used):
  *   - the softmax is causal: window row at absolute position p sees keys <= p;
@@ -407,4 +410,58 @@ int lso_topb(int64_t len, int64_t budget, const float *score, int32_t *keep_idx,
     *keep_cnt = (int32_t)keep;
     free(ln);
     return 0;
+}
+
+/* ------------------------------------------------------------------ O5 --- */
+
+/*
+ * Alg. 3, the Decoding step seen from one attention layer: the newest token's
+ * query attends over the entries its KV head retained at the last retention
+ * step, followed by the tokens generated since then (Alg. 3 adds every
+ * generated token to the retained set), all of them visible:
+ *     out = softmax(scale * q [K_c; K_t]^T) [V_c; V_t].
+ *
+ * q [B,Hq,d]; kc, vc [B,Hkv,cap,d], of which the first cnt[b][kvh] rows are
+ * retained entries (cnt == NULL: all cap rows; rows beyond cnt are never read);
+ * kt, vt [B,Hkv,T,d] the tokens since (T may be 0, then kt, vt may be NULL).
+ * out [B,Hq,d]; lse [B,Hq] natural-log normaliser (optional).  No key at all:
+ * zeros and lse = -inf.
+ */
+int lso_decode(int B, int Hq, int Hkv, int d, int64_t cap, int64_t T, double scale,
+               const float *q, const float *kc, const float *vc, const int32_t *cnt,
+               const float *kt, const float *vt, float *out, float *lse)
+{
+    if (Hq % Hkv || cap < 0 || T < 0) return -1;
+    const int G = Hq / Hkv;
+    int rc = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * Hq; ++bh) {
+        const int b = bh / Hq, h = bh % Hq, kvh = h / G;
+        const int64_t bk = (int64_t)b * Hkv + kvh;
+        const int64_t nc = cnt ? cnt[bk] : cap;
+        if (nc < 0 || nc > cap) { rc = -4; continue; }
+        const int64_t L = nc + T;
+        const float *Q = q + (int64_t)bh * d;
+        double *lg = malloc((L > 0 ? L : 1) * sizeof(double)), *acc = malloc(d * sizeof(double));
+        if (!lg || !acc) { rc = -2; free(lg); free(acc); continue; }
+        double mx = -INFINITY, den = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            const float *K = j < nc ? kc + (bk * cap + j) * d : kt + (bk * T + (j - nc)) * d;
+            double s = 0.0;
+            for (int c = 0; c < d; ++c) s += (double)Q[c] * (double)K[c];
+            lg[j] = s * scale;
+            if (lg[j] > mx) mx = lg[j];
+        }
+        for (int c = 0; c < d; ++c) acc[c] = 0.0;
+        for (int64_t j = 0; j < L; ++j) den += exp(lg[j] - mx);
+        for (int64_t j = 0; j < L; ++j) {
+            const float *V = j < nc ? vc + (bk * cap + j) * d : vt + (bk * T + (j - nc)) * d;
+            const double pr = exp(lg[j] - mx) / den;
+            for (int c = 0; c < d; ++c) acc[c] += pr * (double)V[c];
+        }
+        for (int c = 0; c < d; ++c) out[(int64_t)bh * d + c] = (float)acc[c];
+        if (lse) lse[bh] = L > 0 ? (float)(mx + log(den)) : -INFINITY;
+        free(lg); free(acc);
+    }
+    return rc;
 }

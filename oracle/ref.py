@@ -166,3 +166,26 @@ def topb(score_vec, budget):
     if rc:
         raise RuntimeError(f"lso_topb rc={rc}")
     return keep[:cnt.value]
+
+
+def decode(q, kc, vc, cnt=None, kt=None, vt=None, scale=None, want_lse=True):
+    """Alg. 3 Decoding step of one layer: the newest token attends over the retained entries and the tokens since.
+    q [B,Hq,d]; kc, vc [B,Hkv,cap,d] (first cnt[b,kvh] rows valid; None: all); kt, vt [B,Hkv,T,d] or None.
+    Returns (out [B,Hq,d] float32, lse [B,Hq] float32 or None)."""
+    q, qp = _f(q); kc, kcp = _f(kc); vc, vcp = _f(vc)
+    B, Hq, d = q.shape
+    _, Hkv, cap, _ = kc.shape
+    T = 0 if kt is None else kt.shape[2]
+    if T:
+        kt, ktp = _f(kt); vt, vtp = _f(vt)
+    else:
+        ktp = vtp = None
+    cp = None if cnt is None else _i32(cnt)[1]
+    scale = float(scale) if scale else 1.0 / np.sqrt(d)
+    out = np.empty((B, Hq, d), np.float32)
+    lse = np.empty((B, Hq), np.float32) if want_lse else None
+    rc = lib().lso_decode(B, Hq, Hkv, d, C.c_int64(cap), C.c_int64(T), C.c_double(scale), qp, kcp, vcp, cp, ktp, vtp,
+                          _f(out)[1], None if lse is None else _f(lse)[1])
+    if rc:
+        raise RuntimeError(f"lso_decode rc={rc}")
+    return out, lse

@@ -390,6 +390,92 @@ def test_topb_ties_prefer_small_index(oracle):
     np.testing.assert_array_equal(oracle.topb(s, 5), [0, 1, 2, 3, 5])
 
 
+# ----------------------------------------------------------------------------- O5 decode step
+
+def _decode_case(B=2, Hq=4, Hkv=2, cap=37, T=5, d=16, seed=5):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((B, Hq, d)).astype(np.float32)
+    kc = rng.standard_normal((B, Hkv, cap, d)).astype(np.float32); vc = rng.standard_normal((B, Hkv, cap, d)).astype(np.float32)
+    kt = rng.standard_normal((B, Hkv, T, d)).astype(np.float32); vt = rng.standard_normal((B, Hkv, T, d)).astype(np.float32)
+    cnt = rng.integers(1, cap + 1, (B, Hkv)).astype(np.int32)
+    return q, kc, vc, cnt, kt, vt
+
+
+def test_decode_matches_sdpa(oracle):
+    """Library routine: SDPA over the valid retained rows followed by the tail rows, per query head."""
+    q, kc, vc, cnt, kt, vt = _decode_case()
+    B, Hq, d = q.shape; Hkv = kc.shape[1]; G = Hq // Hkv
+    # rows beyond cnt must never be read
+    kc2, vc2 = kc.copy(), vc.copy()
+    for b in range(B):
+        for g in range(Hkv):
+            kc2[b, g, cnt[b, g]:] = np.nan; vc2[b, g, cnt[b, g]:] = np.nan
+    out, lse = oracle.decode(q, kc2, vc2, cnt, kt, vt)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            K = np.concatenate([kc[b, g, :cnt[b, g]], kt[b, g]]); V = np.concatenate([vc[b, g, :cnt[b, g]], vt[b, g]])
+            ref = _sdpa(q[b, h][None], K, V, np.ones((1, len(K)), bool))[0]
+            np.testing.assert_allclose(out[b, h], ref, rtol=1e-5, atol=1e-6)
+            s = (K.astype(np.float64) @ q[b, h].astype(np.float64)) / math.sqrt(d)
+            np.testing.assert_allclose(lse[b, h], torch.logsumexp(torch.from_numpy(s), 0).item(), rtol=1e-5, atol=1e-6)
+
+
+def test_decode_equals_last_row_of_dense_prefill(oracle):
+    """Cross-pin with lso_attend: with the whole cache retained, the step is the last row of dense causal attention."""
+    B, Hq, Hkv, n, d = 1, 4, 2, 50, 8
+    q, k, v = inputs.make_plain(B, Hq, Hkv, n, 1, d, seed=9)
+    all_idx = np.tile(np.arange(n, dtype=np.int32), (B, Hq, 1)); full = np.full((B, Hq), n, np.int32); none = np.zeros((B, Hq), np.int32)
+    ref, ref_lse = oracle.attend(q, k, v, all_idx, none, all_idx, full, mode=0)
+    out, lse = oracle.decode(q[:, :, 0], k, v)
+    np.testing.assert_allclose(out.reshape(-1, d), ref, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(lse.reshape(-1), ref_lse, rtol=1e-6, atol=1e-7)
+
+
+def test_decode_closed_forms(oracle):
+    B, Hq, Hkv, cap, T, d = 1, 2, 1, 9, 3, 4
+    rng = np.random.default_rng(0)
+    q = rng.standard_normal((B, Hq, d)).astype(np.float32)
+    vc = rng.standard_normal((B, Hkv, cap, d)).astype(np.float32); vt = rng.standard_normal((B, Hkv, T, d)).astype(np.float32)
+    # equal keys: uniform weights, out = mean of all values, lse = logit + log(L)
+    key = rng.standard_normal(d).astype(np.float32)
+    kc = np.tile(key, (B, Hkv, cap, 1)); kt = np.tile(key, (B, Hkv, T, 1))
+    out, lse = oracle.decode(q, kc, vc, None, kt, vt)
+    mean = np.concatenate([vc[0, 0], vt[0, 0]]).astype(np.float64).mean(0)
+    for h in range(Hq):
+        np.testing.assert_allclose(out[0, h], mean, rtol=1e-6, atol=1e-7)
+        logit = float(q[0, h].astype(np.float64) @ key.astype(np.float64)) / math.sqrt(d)
+        np.testing.assert_allclose(lse[0, h], logit + math.log(cap + T), rtol=1e-6)
+    # one tail key far ahead of the rest: the output is its value row
+    kc = np.zeros((B, Hkv, cap, d), np.float32); kt = np.zeros((B, Hkv, T, d), np.float32)
+    qq = np.ones((B, Hq, d), np.float32); kt[0, 0, 1] = 50.0
+    out, _ = oracle.decode(qq, kc, vc, None, kt, vt)
+    np.testing.assert_allclose(out[0, 0], vt[0, 0, 1], rtol=1e-6, atol=1e-6)
+    # a custom scale is applied to the logits
+    out_s, lse_s = oracle.decode(q, kc, vc, None, kt, vt, scale=0.0001)
+    np.testing.assert_allclose(out_s[0, 0], np.concatenate([vc[0, 0], vt[0, 0]]).mean(0), rtol=0, atol=2e-3)
+
+
+def test_decode_split_between_retained_and_tail_is_irrelevant(oracle):
+    """Only the order of the rows matters, not which buffer holds them."""
+    q, kc, vc, _, kt, vt = _decode_case(cap=20, T=6)
+    B, Hkv = kc.shape[:2]
+    full_k = np.concatenate([kc, kt], 2); full_v = np.concatenate([vc, vt], 2)
+    ref, ref_lse = oracle.decode(q, full_k, full_v)
+    out, lse = oracle.decode(q, kc, vc, None, kt, vt)
+    np.testing.assert_array_equal(out, ref); np.testing.assert_array_equal(lse, ref_lse)
+    cnt = np.full((B, Hkv), 11, np.int32)
+    out2, lse2 = oracle.decode(q, full_k, full_v, cnt, full_k[:, :, 11:], full_v[:, :, 11:])
+    np.testing.assert_array_equal(out2, ref); np.testing.assert_array_equal(lse2, ref_lse)
+
+
+def test_decode_no_key_is_zero(oracle):
+    q, kc, vc, _, _, _ = _decode_case(T=0)
+    cnt = np.zeros(kc.shape[:2], np.int32)
+    out, lse = oracle.decode(q, kc, vc, cnt)
+    assert np.all(out == 0) and np.all(np.isneginf(lse))
+
+
 # ----------------------------------------------------------------------------- inputs
 
 def test_inputs_are_seeded_and_storage_exact():
