@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB (10 launches): calibrates the rocprofv3 FETCH_SIZE / "
                          "WRITE_SIZE counters against a kernel of known traffic")
+    ap.add_argument("--decode-probe", action="store_true",
+                    help="only time ls_decode_attend (the decode step over a compressed cache) and print its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by KV-head group with no "
@@ -73,6 +75,38 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": x.numel(), "copy_probe_bytes_written": x.numel(), "launches": 10}))
+        return
+
+    if args.decode_probe:
+        # the decode step of Alg. 3 over a compressed cache (ls_decode_attend), at the decode shape of the
+        # llama70b_16k_b4 workload: budget retained rows + 16 tokens since the retention.  HBM-bound.
+        c5 = inputs.CONFIGS["llama70b_16k_b4"]
+        B, Hq, Hkv, d, cap, T = c5.B, c5.Hq, c5.Hkv, c5.d, args.budget, 16
+        g = torch.Generator(device="cuda").manual_seed(1234)
+        mk = lambda *sh: torch.randn(*sh, device="cuda", generator=g).to(torch.bfloat16)
+        q, kc, vc, kt, vt = mk(B, Hq, d), mk(B, Hkv, cap, d), mk(B, Hkv, cap, d), mk(B, Hkv, T, d), mk(B, Hkv, T, d)
+        cnt = torch.full((B, Hkv), cap, dtype=torch.int32, device="cuda")
+        dshape = binding.make_shape(B, Hq, Hkv, d, cap + T, 1, 1, "bf16")
+        dctx = binding.Context(workspace=binding.decode_workspace_bytes(dshape, cap, T))
+        out = torch.empty_like(q)
+        f = lambda: dctx.ls_decode_attend(dshape, q, kc, vc, cnt, kt, vt, out, None)
+        for _ in range(args.warmup):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        nbytes = 2 * B * Hkv * (cap + T) * d * 2 + 2 * B * Hq * d * 2
+        print(json.dumps({"metric": "decode step over the compressed cache, algorithmic bytes per second", "value": round(nbytes / (ms * 1e-3) / 1e9, 2),
+                          "unit": "GB/s", "ms_per_call": round(ms, 5), "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "llama70b_16k_b4 decode", "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "retained": cap, "since": T},
+                          "roofline": {"kernel": "decode_partial_kernel", "bound": "hbm", "achieved": round(nbytes / (ms * 1e-3) / 1e9, 2), "peak": 8000.0,
+                                       "unit": "GB/s", "frac": round(nbytes / (ms * 1e-3) / 8e12, 4), "bytes": nbytes,
+                                       "note": "per call (two kernels), launch gaps included"}}))
         return
 
     cfg = inputs.CONFIGS[args.workload]

@@ -148,6 +148,30 @@ int ls_kv_compress(ls_ctx* ctx, const ls_shape* shape, int32_t budget,
                    int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* hip_stream);
 
 /*
+ * ls_decode_attend -- Alg. 3, the Decoding step (Sec. 5.2) seen from one attention layer: the newest
+ * token's query attends over the entries its KV head retained at the last ls_kv_compress, followed by
+ * the tokens generated since (Alg. 3 adds every generated token to the retained set); all are visible:
+ *     out = softmax(scale * q [K_c; K_t]^T) [V_c; V_t].
+ *
+ *   shape: B, Hq, Hkv, d, dtype (LS_BF16 only), scale are used; n, n_hat, w are ignored.  Hq/Hkv <= 32.
+ *   q [B,Hq,d]
+ *   k_c, v_c [B,Hkv,cap,d]  retained rows (e.g. k_out / v_out of ls_kv_compress), cap >= 1
+ *   cnt [B,Hkv] int32 device memory: the first cnt rows of each [cap,d] block are valid (values are
+ *        clamped to [0, cap]; e.g. keep_cnt of ls_kv_compress), or NULL for all cap rows
+ *   k_t, v_t [B,Hkv,T,d]    tokens since the retention, in order; T >= 0, NULL allowed when T == 0
+ * Outputs:
+ *   out [B,Hq,d] in dtype; all zeros when a KV head has no key at all (cnt == 0 and T == 0)
+ *   lse [B,Hq] fp32 or NULL: natural log of the softmax denominator (-inf when there is no key)
+ * The caller owns every tensor; the call is asynchronous on hip_stream and uses the context's
+ * workspace (ls_decode_workspace_bytes).  Returns LS_ESHAPE for fp32 or Hq/Hkv > 32.
+ */
+int ls_decode_attend(ls_ctx* ctx, const ls_shape* shape, int32_t cap, int32_t T,
+                     const void* q, const void* k_c, const void* v_c, const int32_t* cnt,
+                     const void* k_t, const void* v_t, void* out, float* lse, void* hip_stream);
+/* Host-only: workspace bytes ls_decode_attend needs for these sizes (0 on a bad shape). */
+size_t ls_decode_workspace_bytes(const ls_shape* shape, int32_t cap, int32_t T);
+
+/*
  * Timing of the sparse attention kernel itself (the dominant kernel of ls_sparse_prefill), for
  * roofline reports.  After ls_profile_enable(ctx, 1) every ls_sparse_prefill call brackets that
  * one kernel launch with HIP events on the call's stream (this creates two events per call, so

@@ -59,6 +59,10 @@ def load_library():
     lib.ls_sparse_prefill.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.ls_kv_compress.restype = C.c_int
     lib.ls_kv_compress.argtypes = [vp, sp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ls_decode_attend.restype = C.c_int
+    lib.ls_decode_attend.argtypes = [vp, sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ls_decode_workspace_bytes.restype = C.c_size_t
+    lib.ls_decode_workspace_bytes.argtypes = [sp, i32, i32]
     lib.ls_debug_copy_compress_score.restype = C.c_int
     lib.ls_debug_copy_compress_score.argtypes = [vp, sp, vp, vp]
     lib.ls_profile_enable.restype = C.c_int
@@ -76,6 +80,10 @@ def make_shape(B, Hq, Hkv, d, n, n_hat, w, dtype, scale=0.0) -> LsShape:
 
 def workspace_bytes(shape: LsShape, budget: int = 0) -> int:
     return int(load_library().ls_workspace_bytes(C.byref(shape), budget))
+
+
+def decode_workspace_bytes(shape: LsShape, cap: int, T: int) -> int:
+    return int(load_library().ls_decode_workspace_bytes(C.byref(shape), cap, T))
 
 
 def _ptr(t):
@@ -139,6 +147,11 @@ class Context:
     def ls_kv_compress(self, shape, budget, q_obs, k, v, keep_idx, keep_cnt, k_out=None, v_out=None):
         self._check(self.lib.ls_kv_compress(self.h, C.byref(shape), budget, _ptr(q_obs), _ptr(k), _ptr(v),
                                             _ptr(keep_idx), _ptr(keep_cnt), _ptr(k_out), _ptr(v_out), _stream()))
+
+    def ls_decode_attend(self, shape, q, k_c, v_c, cnt, k_t, v_t, out, lse=None):
+        T = 0 if k_t is None else k_t.shape[2]
+        self._check(self.lib.ls_decode_attend(self.h, C.byref(shape), k_c.shape[2], T, _ptr(q), _ptr(k_c), _ptr(v_c),
+                                              _ptr(cnt), _ptr(k_t), _ptr(v_t), _ptr(out), _ptr(lse), _stream()))
 
     def profile_enable(self, on=True):
         self._check(self.lib.ls_profile_enable(self.h, 1 if on else 0))

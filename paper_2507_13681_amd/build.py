@@ -7,7 +7,7 @@ import subprocess
 _DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_DIR, "csrc")
 LIB = os.path.join(_DIR, "libloopserve.so")
-SOURCES = ["ls_api.hip", "ls_score.hip", "ls_select.hip", "ls_prefill.hip"]
+SOURCES = ["ls_api.hip", "ls_score.hip", "ls_select.hip", "ls_prefill.hip", "ls_decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -291,6 +291,56 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
     return LS_OK;
 }
 
+namespace {
+// split of the key axis for ls_decode_attend: chunks of whole 128-key rounds (4 waves x 32 keys),
+// enough workgroups to cover the chip about twice (more, shorter chunks measured slower: more partials to merge)
+void decode_split(const ls_shape* s, int32_t cap, int32_t T, int* nsplit, int* chunk) {
+    const int64_t L = (int64_t)cap + T;
+    const int64_t rounds = (L + 127) / 128;
+    int64_t want = 512 / ((int64_t)s->B * s->Hkv);
+    if (want < 1) want = 1;
+    if (want > rounds) want = rounds;
+    const int64_t per = (rounds + want - 1) / want;
+    *chunk = (int)(per * 128);
+    *nsplit = (int)((rounds + per - 1) / per);
+}
+}  // namespace
+
+size_t ls_decode_workspace_bytes(const ls_shape* s, int32_t cap, int32_t T) {
+    if (!s || s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->Hq % s->Hkv || (s->d != 64 && s->d != 128) || cap < 1 || T < 0) return 0;
+    int nsplit, chunk;
+    decode_split(s, cap, T, &nsplit, &chunk);
+    return up((size_t)s->B * s->Hq * nsplit * (s->d + 2) * 4) + ALIGN;
+}
+
+int ls_decode_attend(ls_ctx* c, const ls_shape* s, int32_t cap, int32_t T, const void* q, const void* k_c, const void* v_c,
+                     const int32_t* cnt, const void* k_t, const void* v_t, void* out, float* lse, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (!s) return fail(c, LS_ESHAPE, "ls_decode_attend: shape is NULL");
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->Hq % s->Hkv) return fail(c, LS_ESHAPE, "ls_decode_attend: need positive B, Hq, Hkv with Hkv dividing Hq");
+    if (s->d != 64 && s->d != 128) return fail(c, LS_ESHAPE, "ls_decode_attend: d must be 64 or 128");
+    if (s->dtype != LS_BF16) return fail(c, LS_ESHAPE, "ls_decode_attend: dtype must be LS_BF16");
+    if (s->Hq / s->Hkv > 32) return fail(c, LS_ESHAPE, "ls_decode_attend: at most 32 query heads per KV head");
+    if ((int64_t)s->B * s->Hkv > 65535) return fail(c, LS_ESHAPE, "ls_decode_attend: B * Hkv too large");
+    if (cap < 1 || T < 0 || (int64_t)cap + T > 2147483000LL / 256) return fail(c, LS_ESHAPE, "ls_decode_attend: need cap >= 1, T >= 0, cap + T < 2^23");
+    if (!q || !k_c || !v_c || !out || (T > 0 && (!k_t || !v_t))) return fail(c, LS_EINVAL, "ls_decode_attend: NULL tensor");
+    if (!aligned16(q) || !aligned16(k_c) || !aligned16(v_c) || !aligned16(k_t) || !aligned16(v_t) || !aligned16(out))
+        return fail(c, LS_EINVAL, "ls_decode_attend: misaligned tensor");
+    ls::DecodeArgs a{};
+    a.q = q; a.kc = k_c; a.vc = v_c; a.kt = k_t; a.vt = v_t; a.cnt = cnt; a.out = out; a.lse = lse;
+    a.B = s->B; a.Hq = s->Hq; a.Hkv = s->Hkv; a.G = s->Hq / s->Hkv; a.cap = cap; a.T = T;
+    a.scale_log2e = scale_log2e(s);
+    decode_split(s, cap, T, &a.nsplit, &a.chunk);
+    if (ls::decode_smem_bytes(s->d, a.G) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_decode_attend: group too large for LDS");
+    Bump bp{c->ws, c->ws_bytes, 0};
+    a.part = bp.take<float>((size_t)s->B * s->Hq * a.nsplit * (s->d + 2));
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_decode_attend: workspace of %zu bytes is too small", c->ws_bytes);
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_decode_attend: hipSetDevice failed");
+    hipError_t e = ls::run_decode(a, s->d, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_decode_attend: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
 int ls_profile_enable(ls_ctx* c, int on) {
     if (!c) return LS_EINVAL;
     (void)hipSetDevice(c->device);

@@ -57,7 +57,7 @@ __device__ __forceinline__ void zero_frag(Frag<float>& f) {
     for (int i = 0; i < 8; ++i) f.v[i] = 0.f;
 }
 
-// float -> bf16 bits, round to nearest even (inputs here are finite and non-negative).
+// float -> bf16 bits, round to nearest even (finite inputs).
 __device__ __forceinline__ uint16_t f2bf(float x) {
     uint32_t u = __builtin_bit_cast(uint32_t, x);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -76,6 +76,33 @@ __device__ __forceinline__ void pack_frag(Frag<bf16_t>& f, const float* p) {
 __device__ __forceinline__ void pack_frag(Frag<float>& f, const float* p) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) f.v[i] = p[i];
+}
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// One wave-wide global -> LDS transfer (global_load_lds_dwordx4): lane l fetches 16 bytes and they land
+// at LDS byte address lds + 16 * l; `lds` (and `gbase`) are wave-uniform.  Written as asm statements so
+// that the compiler does not count the transfers among the memory operations it tracks: it cannot tell
+// which LDS bytes a transfer fills and would make every later LDS read wait for all outstanding
+// transfers, serialising a prefetch with the work on the data already there.  A kernel waits for its
+// transfers itself (wait_transfers, then a barrier if other waves read the data).  M0 is used by
+// nothing else in these kernels.
+__device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t voff, uint32_t lds) {   // address = gbase + voff
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void dma16(const unsigned char* gptr, uint32_t lds) {                    // per-lane address
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void wait_transfers() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// LDS transpose read of a bf16 tile stored row-major: in a block of 16 lanes, lane s addresses 4
+// consecutive 16-bit values and lane L receives value L % 4 of the lanes L/4, L/4+4, L/4+8, L/4+12.
+// Two reads (rows r .. and r + 8 ..) give a lane the eight contraction-index values of a fragment.
+__device__ __forceinline__ void load_frag_tr(Frag<bf16_t>& f, const unsigned char* lo_addr, const unsigned char* hi_addr) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lo_addr));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(hi_addr));
+    struct U { s16x4 a, b; } u = {lo, hi};
+    f.v = __builtin_bit_cast(bf16x8, u);
 }
 
 __device__ __forceinline__ float to_float(bf16_t x) { return bf2f(x.bits); }

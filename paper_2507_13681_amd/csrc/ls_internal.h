@@ -83,7 +83,21 @@ struct PrefillArgs {
     int qcap;                 // entries per queue
 };
 
+struct DecodeArgs {
+    const void *q;            // [B][Hq][d]
+    const void *kc, *vc;      // [B][Hkv][cap][d] retained entries (first cnt rows valid)
+    const void *kt, *vt;      // [B][Hkv][T][d] tokens since the retention
+    const int32_t* cnt;       // [B][Hkv] or NULL (all cap rows)
+    void* out;                // [B][Hq][d]
+    float* lse;               // [B][Hq] or NULL
+    float* part;              // [B*Hkv][nsplit][G][d + 2] per-split output, reference, normaliser
+    int B, Hq, Hkv, G, cap, T, nsplit, chunk;
+    float scale_log2e;
+};
+
 hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st);
+hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st);
+size_t decode_smem_bytes(int d, int G);
 size_t score_lines_smem(int w);
 hipError_t run_select(const SelectArgs& a, hipStream_t st);
 hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st);

@@ -628,20 +628,6 @@ struct DirectCfg {
     __device__ static constexpr int vswz(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-
-// One wave-wide global -> LDS transfer: lane l fetches the 16 bytes at gbase + voff and they land at
-// LDS byte address lds + 16 * l.  gbase and lds are wave-uniform.  Written as an asm statement so that
-// the compiler does not count the transfer among the memory operations it tracks: it cannot tell which
-// LDS bytes a transfer fills and would make every later LDS read wait for all outstanding transfers,
-// serialising the prefetch of the next tile with the products of the current one.  The kernel waits
-// for its transfers itself (wait_transfers before the barrier that publishes a buffer).  M0 is used by
-// nothing else in these kernels.
-__device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t voff, uint32_t lds) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory");
-}
-__device__ __forceinline__ void wait_transfers() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 template <int D>
 __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(PrefillArgs a) {
     using C = DirectCfg<D>;
