@@ -44,9 +44,29 @@ constexpr int PREFILL_THREADS = 256;
 //           [64j-63, 64j+127] is selected, bit1 = all of them are (and none is cut off at 0 or n-1)
 //   hflag : [BH] bytes, bit0 = every diagonal 0..n-1 is selected (the mask is plain causal)
 // ---------------------------------------------------------------------------------------------
+// Exclusive prefix sum over the 1024 threads of a workgroup (wave shuffles + one LDS round).
+// `wsum` must hold 16 words; returns the sum of `v` over the threads before this one and, in
+// `total`, the sum over all threads.
+__device__ __forceinline__ uint32_t block_scan_1024(uint32_t v, uint32_t* wsum, uint32_t& total) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
+    __syncthreads();                                       // wsum may still be read from an earlier call
+    if (lane == 63) wsum[wv] = inc;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { const uint32_t t = wsum[w]; all += t; if (w < wv) before += t; }
+    total = all;
+    return before + inc - v;
+}
+
+constexpr int LS_MAX_TAB = 262144 / 64 + 8;  // table entries at the largest supported context
 __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     extern __shared__ uint32_t sm[];
     __shared__ int total_bits;
+    __shared__ uint8_t tabs[LS_MAX_TAB];
     const int bh = blockIdx.x;
     const int64_t n = a.n;
     const int words = a.words;
@@ -56,9 +76,12 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     for (int i = tid; i < words; i += blockDim.x) sm[i] = 0u;
     if (tid == 0) total_bits = 0;
     __syncthreads();
-    for (int i = tid; i < ns; i += blockDim.x) {
-        const int32_t o = si[i];
-        if (o >= 0 && o < n) atomicOr(&sm[o >> 5], 1u << (o & 31));
+    for (int i0 = tid; i0 < ns; i0 += 8 * 1024) {          // eight independent loads in flight per thread
+        int32_t o8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const int i = i0 + j * 1024; o8[j] = i < ns ? si[i] : -1; }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) if (o8[j] >= 0 && o8[j] < n) atomicOr(&sm[o8[j] >> 5], 1u << (o8[j] & 31));
     }
     __syncthreads();
     int mine = 0;
@@ -85,38 +108,28 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
         if (cnt > 0) f |= 1;
         if (!cut && hi >= lo && cnt == (int)(hi - lo + 1) && hi == 64 * j + 127) f |= 2;
         a.tab[(int64_t)bh * a.tab_len + e] = f;
+        tabs[e] = f;                                       // LDS copy for the counts below
     }
     __syncthreads();
-    if (tid == 0) a.hflag[bh] = (total_bits == (int)n) ? 1 : 0;
-    // cost estimate: table entries with a selected diagonal (key blocks a late row block visits) plus
-    // packed column tiles
-    __shared__ int active_entries;
-    if (tid == 0) active_entries = 0;
-    __syncthreads();
-    int act = 0;
-    for (int e = tid; e < a.tab_len; e += blockDim.x) act += a.tab[(int64_t)bh * a.tab_len + e] & 1;
-    atomicAdd(&active_entries, act);
-    __syncthreads();
+    // prefix counts of active entries: pref[e] = number of active entries below e
+    __shared__ uint32_t wsum[16];
+    const int chunk = (a.tab_len + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int e0 = tid * chunk < a.tab_len ? tid * chunk : a.tab_len, e1 = (e0 + chunk < a.tab_len) ? e0 + chunk : a.tab_len;
+    int mine2 = 0;
+    for (int e = e0; e < e1; ++e) mine2 += tabs[e] & 1;
+    uint32_t active_entries;
+    uint32_t run = block_scan_1024((uint32_t)mine2, wsum, active_entries);
+    uint16_t* pref = a.pref + (int64_t)bh * (a.tab_len + 1);
+    for (int e = e0; e < e1; ++e) { pref[e] = (uint16_t)run; run += tabs[e] & 1; }
+    if (e1 == a.tab_len && e0 < a.tab_len) pref[a.tab_len] = (uint16_t)run;
+    // head flag and cost estimate: table entries with a selected diagonal (key blocks a late row block
+    // visits) plus packed column tiles
     if (tid == 0) {
+        a.hflag[bh] = (total_bits == (int)n) ? 1 : 0;
         int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
         if (total_bits == (int)n) nv = 0;
-        a.cost[bh] = (uint32_t)(active_entries + (nv + 63) / 64 + 1);
+        a.cost[bh] = (uint32_t)((int)active_entries + (nv + 63) / 64 + 1);
     }
-    // prefix counts of active entries: pref[e] = number of active entries below e
-    __syncthreads();
-    __shared__ uint32_t cnt[1024];                         // per-thread chunk totals
-    const int chunk = (a.tab_len + (int)blockDim.x - 1) / (int)blockDim.x;
-    const int e0 = tid * chunk, e1 = (e0 + chunk < a.tab_len) ? e0 + chunk : a.tab_len;
-    int mine2 = 0;
-    for (int e = e0; e < e1; ++e) mine2 += a.tab[(int64_t)bh * a.tab_len + e] & 1;
-    cnt[tid] = mine2;
-    __syncthreads();
-    if (tid == 0) { uint32_t run = 0; for (int i = 0; i < (int)blockDim.x; ++i) { const uint32_t t = cnt[i]; cnt[i] = run; run += t; } }
-    __syncthreads();
-    uint32_t run = cnt[tid];
-    uint16_t* pref = a.pref + (int64_t)bh * (a.tab_len + 1);
-    for (int e = e0; e < e1; ++e) { pref[e] = (uint16_t)run; run += a.tab[(int64_t)bh * a.tab_len + e] & 1; }
-    if (e1 == a.tab_len && e0 < a.tab_len) pref[a.tab_len] = (uint16_t)run;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -196,9 +209,14 @@ __global__ __launch_bounds__(SCHED_THREADS) void sched_kernel(SchedArgs a) {
     for (int64_t it = tid; it < items; it += SCHED_THREADS)
         atomicAdd(&hist[4095 - item_cost(heads[it / a.nqb], (int)(it % a.nqb))], 1u);
     __syncthreads();
-    if (tid == 0) {                                        // exclusive scan in decreasing-cost order
-        uint32_t run = 0;
-        for (int i = 0; i < 4096; ++i) { const uint32_t t = hist[i]; hist[i] = run; run += t; }
+    {                                                      // exclusive scan in decreasing-cost order
+        __shared__ uint32_t wsum[16];
+        uint32_t h4[4], mine = 0, all;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { h4[q] = hist[4 * tid + q]; mine += h4[q]; }
+        uint32_t run = block_scan_1024(mine, wsum, all);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { hist[4 * tid + q] = run; run += h4[q]; }
     }
     __syncthreads();
     for (int64_t it = tid; it < items; it += SCHED_THREADS) {

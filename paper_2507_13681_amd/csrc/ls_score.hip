@@ -237,23 +237,37 @@ __global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguou
     const int bh = blockIdx.x, tid = threadIdx.x;
     const int64_t n = a.n;
     if (contiguous) {
-        for (int64_t o = tid; o < n; o += blockDim.x) {
-            int64_t lo = n - a.w - o; if (lo < 0) lo = 0;
-            const int64_t kA = lo / SB, kB = (n - 1 - o) / SB;
-            const float* pa = a.spart + (((kA & 1) * a.BH + bh) * n + o) * 2;
-            float s = pa[0], m = pa[1];
-            if (kB != kA) {
+        for (int64_t o0 = tid; o0 < n; o0 += 8 * 1024) {       // eight diagonals per thread, all loads first
+            float sa[8], ma[8], sb[8], mb[8]; bool two[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int64_t o = o0 + j * 1024 < n ? o0 + j * 1024 : n - 1;
+                int64_t lo = n - a.w - o; if (lo < 0) lo = 0;
+                const int64_t kA = lo / SB, kB = (n - 1 - o) / SB;
+                const float* pa = a.spart + (((kA & 1) * a.BH + bh) * n + o) * 2;
                 const float* pb = a.spart + (((kB & 1) * a.BH + bh) * n + o) * 2;
-                s = s + pb[0];                         // lower key block first
-                m = fmaxf(m, pb[1]);
+                two[j] = kB != kA;
+                sa[j] = pa[0]; ma[j] = pa[1]; sb[j] = pb[0]; mb[j] = pb[1];
             }
-            a.slash[(int64_t)bh * n + o] = s;
-            a.smax[(int64_t)bh * n + o] = m;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int64_t o = o0 + j * 1024;
+                if (o < n) {
+                    a.slash[(int64_t)bh * n + o] = two[j] ? sa[j] + sb[j] : sa[j];      // lower key block first
+                    a.smax[(int64_t)bh * n + o] = two[j] ? fmaxf(ma[j], mb[j]) : ma[j];
+                }
+            }
         }
     }
     // total = sum of the column sums, fixed tree order
     float acc = 0.f;
-    for (int64_t i = tid; i < n; i += blockDim.x) acc += a.vert[(int64_t)bh * n + i];
+    for (int64_t i0 = tid; i0 < n; i0 += 8 * 1024) {           // same order of additions as one element per trip
+        float v8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const int64_t i = i0 + j * 1024; v8[j] = i < n ? a.vert[(int64_t)bh * n + i] : 0.f; }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) if (i0 + j * 1024 < n) acc += v8[j];
+    }
     red[tid] = acc;
     __syncthreads();
     for (int s = 512; s > 0; s >>= 1) {

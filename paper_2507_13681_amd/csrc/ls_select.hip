@@ -449,7 +449,13 @@ __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
     for (int i = tid; i < words; i += 1024) bm[i] = 0u;
     if (tid == 0) carry = 0u;
     __syncthreads();
-    for (int i = tid; i < cnt; i += 1024) { const int32_t x = sorted_idx[i]; atomicOr(&bm[x >> 5], 1u << (x & 31)); }
+    for (int i0 = tid; i0 < cnt; i0 += 8 * 1024) {          // eight independent loads in flight per thread
+        int32_t x8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const int i = i0 + j * 1024; x8[j] = i < cnt ? sorted_idx[i] : -1; }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) if (x8[j] >= 0) atomicOr(&bm[x8[j] >> 5], 1u << (x8[j] & 31));
+    }
     __syncthreads();
     for (int w0 = 0; w0 < words; w0 += 1024) {
         const int wd = w0 + tid;
