@@ -3,7 +3,7 @@
 One step = one pass of the whole path for one attention layer on one synthetic batch:
     ls_score -> ls_select -> ls_sparse_prefill   (online-sparsified prefill of the newest turn)
     + one ls_kv_compress call                    (decode-time re-scoring of the same cache; second stream)
-with every input already resident in HBM.  Prints ONE JSON line (see README).
+with every input already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload multiturn_32k] [--no-cpu]
 """
@@ -62,7 +62,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by KV-head group with no "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

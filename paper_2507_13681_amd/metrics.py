@@ -36,3 +36,17 @@ def selection_cells(n: int, n_hat: int, sel: dict) -> np.ndarray:
 
 def causal_cells(n: int, n_hat: int) -> int:
     return n_hat * (n - n_hat) + n_hat * (n_hat + 1) // 2
+
+
+def coverage_from_lse(lse_selected, lse_dense) -> np.ndarray:
+    """Share of each row's attention mass that a selection keeps (the left side of Eq. 1, per row).
+
+    Both arguments are natural-log softmax denominators of the same rows: over the allowed cells
+    (ls_sparse_prefill with the selection) and over all visible cells (ls_sparse_prefill with every
+    diagonal selected).  Their ratio is the sum of the dense attention weights over the allowed
+    cells.  A row without any allowed cell (lse = -inf) keeps 0."""
+    a = np.asarray(lse_selected, np.float64)
+    b = np.asarray(lse_dense, np.float64)
+    with np.errstate(invalid="ignore"):
+        c = np.exp(a - b)
+    return np.where(np.isfinite(a), c, 0.0)
