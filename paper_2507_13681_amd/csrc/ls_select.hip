@@ -337,6 +337,28 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     wait_ready(0, 0);
     wait_ready(1, 0);
 
+    // What the lanes need of a list when its head is at `h`: entry h + lane (weight, overlap prefix, length)
+    // and the head's own three values.  Re-read only when the head of that list moves; the read for the
+    // head position after the current run is issued before the run's sums are settled, so its LDS latency
+    // hides behind them.
+    struct View { float cw, pre, cl, w0, l0, ol0; bool ok, has; };
+    auto view = [&](int l, int h) {
+        const WalkWin& W = win[l][curw[l] & 1];
+        const int base = curw[l] * WALK_STRIDE;
+        View r;
+        const int i = h + lane;
+        r.ok = i < n && (i - base) < WALK_WIN;
+        const int ii = r.ok ? i - base : 0;
+        r.cw = W.cw[ii]; r.pre = W.pre[ii]; r.cl = W.cl[ii];
+        r.has = h < n;
+        const int hh = r.has ? h - base : 0;
+        r.w0 = r.has ? W.cw[hh] : 0.f;                     // an exhausted list: no weight, and its overlap sum
+        r.l0 = r.has ? W.cl[hh] : 1.f;                     // sits right behind its last line
+        r.ol0 = W.pre[h - base];
+        return r;
+    };
+    View S = view(0, 0), V = view(1, 0);
+
     while (!failed) {
         const int is = head[0], iv = head[1];
         if (!(sum < target) || (is >= n && iv >= n)) break;
@@ -346,34 +368,27 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the window left behind
             if (lane == 0) walk_st(&sync->cur[0], curw[0]);
             wait_ready(0, curw[0]);
+            if (failed) break;
+            S = view(0, is);
         }
         if (iv < n && iv >= (curw[1] + 1) * WALK_STRIDE) {
             ++curw[1];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             if (lane == 0) walk_st(&sync->cur[1], curw[1]);
             wait_ready(1, curw[1]);
+            if (failed) break;
+            V = view(1, iv);
         }
-        if (failed) break;
-        const WalkWin& S = win[0][curw[0] & 1];
-        const WalkWin& V = win[1][curw[1] & 1];
-        const int bs = curw[0] * WALK_STRIDE, bv = curw[1] * WALK_STRIDE;
-        const bool s_has = is < n, v_has = iv < n;
-        const int hs = s_has ? is - bs : 0, hv = v_has ? iv - bv : 0;      // head positions inside the windows
-        // frozen heads of both lists (an exhausted list's overlap sum sits right behind its last line)
-        const float ws0 = s_has ? S.cw[hs] : 0.f, ls0 = s_has ? S.cl[hs] : 1.f;
-        const float wv0 = v_has ? V.cw[hv] : 0.f, lv0 = v_has ? V.cl[hv] : 1.f;
-        const float ols0 = S.pre[is - bs], olv0 = V.pre[iv - bv];
+        const bool s_has = S.has, v_has = V.has;
         // lane j: decision if the walk has taken j more slashes (iv frozen)
         int i = is + lane;
-        bool ok = i < n && (i - bs) < WALK_WIN;
-        int ii = ok ? i - bs : 0;
-        float ds = __fsub_rn(S.cw[ii], olv0);
-        float dv = __fsub_rn(wv0, S.pre[ii]);
-        float cs = __fsub_rn(S.cl[ii], (float)iv); if (cs < 1.0f) cs = 1.0f;
-        float cv = __fsub_rn(lv0, (float)i); if (cv < 1.0f) cv = 1.0f;
+        float ds = __fsub_rn(S.cw, V.ol0);
+        float dv = __fsub_rn(V.w0, S.pre);
+        float cs = __fsub_rn(S.cl, (float)iv); if (cs < 1.0f) cs = 1.0f;
+        float cv = __fsub_rn(V.l0, (float)i); if (cv < 1.0f) cv = 1.0f;
         bool take = !v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
         bool dead = !(ds > 0.f) && (!v_has || !(dv > 0.f));
-        uint64_t bal = __ballot(ok && take);
+        uint64_t bal = __ballot(S.ok && take);
         int run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
         float gain = ds;
         int which = 0;
@@ -381,15 +396,13 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             // the head pick is a vertical; lane j: decision if j more verticals are taken (is frozen)
             which = 1;
             i = iv + lane;
-            ok = i < n && (i - bv) < WALK_WIN;
-            ii = ok ? i - bv : 0;
-            dv = __fsub_rn(V.cw[ii], ols0);
-            ds = __fsub_rn(ws0, V.pre[ii]);
-            cv = __fsub_rn(V.cl[ii], (float)is); if (cv < 1.0f) cv = 1.0f;
-            cs = __fsub_rn(ls0, (float)i); if (cs < 1.0f) cs = 1.0f;
+            dv = __fsub_rn(V.cw, S.ol0);
+            ds = __fsub_rn(S.w0, V.pre);
+            cv = __fsub_rn(V.cl, (float)is); if (cv < 1.0f) cv = 1.0f;
+            cs = __fsub_rn(S.l0, (float)i); if (cs < 1.0f) cs = 1.0f;
             take = !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
             dead = !(dv > 0.f) && (!s_has || !(ds > 0.f));
-            bal = __ballot(ok && take);
+            bal = __ballot(V.ok && take);
             run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
             gain = dv;
         }
@@ -400,17 +413,23 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         if (early && deadb) stop_dead = __ffsll((unsigned long long)deadb) - 1;
         // picks 0 .. limit-1 are applied; the running sum is accumulated pick by pick
         const int limit = run < stop_dead ? run : stop_dead;
+        // the list's view after the run (used only if the whole run is applied and the walk goes on; a
+        // window change re-reads it)
+        const View nxt = view(which, head[which] + limit);
         // Lane j ends up with the running sum after pick j: x_j = x_{j-1} + gain_j, lane 0 starting from
         // `sum`.  One pass of "take the left neighbour's value and add my gain" over all lanes settles one
         // more lane, in order, so `limit` passes reproduce the pick-by-pick additions exactly; the first
         // lane whose sum reaches the target is the pick the loop of the definition stops after.
+        // (Lane 0 has no left neighbour: the shift hands it 0 and its addend is sum + gain_0, so it
+        // holds exactly that.)
+        const float addend = lane == 0 ? __fadd_rn(sum, gain) : gain;
         float x = 0.f;
         for (int p0 = 0; p0 < limit; p0 += 8) {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
-                    __builtin_bit_cast(int, sum), __builtin_bit_cast(int, x), 0x138 /* wave_shr:1 */, 0xF, 0xF, false));
-                x = __fadd_rn(left, gain);
+                    0, __builtin_bit_cast(int, x), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+                x = __fadd_rn(left, addend);
             }
         }
         const uint64_t lanes = limit >= 64 ? ~0ull : ((1ull << limit) - 1ull);
@@ -422,6 +441,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         const bool exhausted = !reached && stop_dead < run;      // the pick after the last one has no positive gain
         head[which] += taken;
         if (exhausted) { head[0] = n; head[1] = n; break; }
+        if (which == 0) S = nxt; else V = nxt;
     }
     if (lane == 0) {
         walk_st(&sync->done, 1);
