@@ -198,7 +198,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 // add and one compare per pick, on values already sitting in the lanes' registers.
 // Each pick therefore sees exactly the operands, operation order and roundings of the definition.
 constexpr int WALK_THREADS = 128;              // wave 0 walks; wave 1 fills the list windows ahead of it
-constexpr int WALK_WIN = 1024;                 // window of a list kept in LDS
+constexpr int WALK_WIN = 512;                  // window of a list kept in LDS
 constexpr int WALK_STRIDE = WALK_WIN - 128;    // window k of a list covers sorted positions [k * STRIDE, k * STRIDE + WIN)
 constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the two waves (never reached; about a second)
 
