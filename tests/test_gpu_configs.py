@@ -175,3 +175,46 @@ def test_config5_llama70b_decode_compress(oracle):
                         assert np.all(np.abs(ref["score"][b, j][diff] - thr) <= 1e-3 * thr)
             checked += 1
     assert checked == 3
+
+
+def test_maximum_context_length(oracle):
+    """n = LS_MAX_N (262144): 32 sort segments, the largest diagonal bitmap and activity table, a short newest turn
+    so that the oracle stays quick.  Structured inputs (sinks, heavy columns, a local band) as in the workloads."""
+    cfg = inputs.scaled(inputs.CONFIGS["llama8b_8k"], n=262144, Hq=2, Hkv=1, turns=256, name="max_n")
+    assert cfg.n_hat == 1024
+    print(f"[max_n] generating inputs n={cfg.n} n_hat={cfg.n_hat}", flush=True)
+    q, k, v, _ = inputs.make_inputs(cfg)
+    pipe = Pipeline(q, k, v, cfg.w, cfg.dtype)
+    sc_ref = oracle.score(q[:, :, -cfg.w:], k)
+    sc_dev = pipe.score()
+    check_scores(host(sc_dev), sc_ref, cfg.w)
+    for alpha in (0.9, 0.999):
+        sel_ref = oracle.select(sc_ref, cfg.n_hat, alpha)
+        sel_dev = pipe.select(sc_dev, alpha, accounted=False)
+        sel_gpu = host(sel_dev)
+        tolerated = check_selection(sel_gpu, sel_ref, sc_ref, alpha)
+        print(f"[max_n] alpha={alpha}: counts v {sel_gpu['v_cnt'].ravel().tolist()} s {sel_gpu['s_cnt'].ravel().tolist()}, tolerated {tolerated}", flush=True)
+        out, lse = pipe.prefill(sel_dev)
+        torch.cuda.synchronize()
+        rows = sample_rows(cfg, 12, np.random.default_rng(1))
+        check_attention(oracle, cfg, q, k, v, sel_gpu, out, lse, rows, mode=1)
+
+
+def test_first_turn_prefill(oracle):
+    """The first turn of a dialogue: every row is new (n_hat = n), so the causal triangle starts at row 0."""
+    cfg = inputs.scaled(inputs.CONFIGS["llama8b_8k"], n=1800, Hq=4, Hkv=2, turns=1, heavy_lo=8, heavy_hi=24, span=128, name="first_turn")
+    assert cfg.n_hat == cfg.n
+    q, k, v, _ = inputs.make_inputs(cfg)
+    pipe = Pipeline(q, k, v, cfg.w, cfg.dtype)
+    sc_ref = oracle.score(q[:, :, -cfg.w:], k)
+    sc_dev = pipe.score()
+    check_scores(host(sc_dev), sc_ref, cfg.w)
+    sel_ref = oracle.select(sc_ref, cfg.n_hat, 0.9)
+    sel_dev = pipe.select(sc_dev, 0.9, accounted=False)
+    sel_gpu = host(sel_dev)
+    check_selection(sel_gpu, sel_ref, sc_ref, 0.9)
+    print("[first_turn] prefill of all rows", flush=True)
+    out, lse = pipe.prefill(sel_dev)
+    torch.cuda.synchronize()
+    rows = np.arange(cfg.B * cfg.Hq * cfg.n_hat, dtype=np.int64)
+    check_attention(oracle, cfg, q, k, v, sel_gpu, out, lse, rows, mode=1)
