@@ -86,7 +86,7 @@ inline int tab_len_of(int64_t n) { return (int)(n / 64) + 4; }
 size_t ws_prefill(const ls_shape* s) {
     const size_t BH = (size_t)s->B * s->Hq;
     const size_t items = BH * (size_t)(s->n / 128 + 2);          // (head, row block) work items, upper bound
-    return up(BH * (size_t)words_of(s->n) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH) + up(BH * 4) + up(BH * (size_t)(tab_len_of(s->n) + 1) * 2) +
+    return up(BH * (size_t)(words_of(s->n) + 1) * 4) + up(BH * (size_t)tab_len_of(s->n)) + up(BH) + up(BH * 4) + up(BH * (size_t)(tab_len_of(s->n) + 1) * 2) +
            up(8 * items * 4) + 2 * up(8 * 4);
 }
 size_t ws_compress(const ls_shape* s) {
@@ -205,7 +205,7 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     if (ls::prefill_smem_bytes(s->dtype, s->d, words, tab_len) > 160 * 1024)
         return fail(c, LS_ESHAPE, "ls_sparse_prefill: n too large for the LDS bitmaps");
     Bump bp{c->ws, c->ws_bytes, 0};
-    uint32_t* obits = bp.take<uint32_t>((size_t)BH * words);
+    uint32_t* obits = bp.take<uint32_t>((size_t)BH * (words + 1));
     uint8_t* hflag = bp.take<uint8_t>((size_t)BH);
     uint32_t* cost = bp.take<uint32_t>((size_t)BH);
     uint16_t* pref = bp.take<uint16_t>((size_t)BH * (tab_len + 1));

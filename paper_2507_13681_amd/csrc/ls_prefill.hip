@@ -39,7 +39,7 @@ constexpr int PREFILL_THREADS = 256;
 
 // ---------------------------------------------------------------------------------------------
 // plan: per (batch, head) bitmap of the selected diagonals, the per-j activity table, a head flag.
-//   obits : [BH][words] uint32, bit o of word o/32; words = n/32 rounded up + 8 zero words
+//   obits : [BH][words + 1] uint32: one zero word, then bit o in word 1 + o/32; words = n/32 rounded up + 8 zero words
 //   tab   : [BH][tab_len] bytes, entry j+1 for j = -1 .. ; bit0 = some diagonal of
 //           [64j-63, 64j+127] is selected, bit1 = all of them are (and none is cut off at 0 or n-1)
 //   hflag : [BH] bytes, bit0 = every diagonal 0..n-1 is selected (the mask is plain causal)
@@ -85,7 +85,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     }
     __syncthreads();
     int mine = 0;
-    for (int i = tid; i < words; i += blockDim.x) { a.obits[(int64_t)bh * words + i] = sm[i]; mine += __popc(sm[i]); }
+    uint32_t* og = a.obits + (int64_t)bh * (words + 1);       // one zero word, then the bitmap
+    if (tid == 0) og[0] = 0u;
+    for (int i = tid; i < words; i += blockDim.x) { og[i + 1] = sm[i]; mine += __popc(sm[i]); }
     atomicAdd(&total_bits, mine);
     // activity table
     for (int e = tid; e < a.tab_len; e += blockDim.x) {
@@ -341,8 +343,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
     const T* Qg = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.n_hat * D;
 
     // diagonal bitmap and activity table of this head -> LDS
-    for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i + 1] = a.obits[(int64_t)bh * a.words + i];
-    if (tid == 0) ob[0] = 0u;
+    for (int i = tid; i < a.words + 1; i += PREFILL_THREADS) ob[i] = a.obits[(int64_t)bh * (a.words + 1) + i];
     for (int i = tid; i < a.tab_len; i += PREFILL_THREADS) tab[i] = a.tab[(int64_t)bh * a.tab_len + i];
 
     // this lane's query row and its fragments
@@ -646,14 +647,17 @@ struct DirectCfg {
     __device__ static constexpr int vswz(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
-template <int D>
+// OBLDS: the head's diagonal bitmap is copied to LDS (short contexts); otherwise it is read from global
+// memory where needed (the masks of a tile are computed one tile ahead, under the transfer wait), which
+// keeps two workgroups per CU at long contexts.
+template <int D, bool OBLDS>
 __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(PrefillArgs a) {
     using C = DirectCfg<D>;
     using T = bf16_t;
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* tiles = smem;                                         // [2][TILE_BYTES]
-    uint32_t* ob = reinterpret_cast<uint32_t*>(smem + 2 * C::TILE_BYTES);
-    int32_t* colring = reinterpret_cast<int32_t*>(ob + a.words + 1);     // [3][64]; ob = zero word + bitmap
+    uint32_t* ob_lds = reinterpret_cast<uint32_t*>(smem + 2 * C::TILE_BYTES);
+    int32_t* colring = reinterpret_cast<int32_t*>(ob_lds + (OBLDS ? a.words + 1 : 0));   // [3][64]
     int32_t* wcnt = colring + 192;                                       // [8]
     uint16_t* kbl = reinterpret_cast<uint16_t*>(wcnt + 8);               // [tab_len] active key blocks | flags << 14
     uint8_t* tab = reinterpret_cast<uint8_t*>(kbl + ((a.tab_len + 7) & ~7));   // [tab_len] this head's per-j table
@@ -705,8 +709,9 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
     const T* Qg = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.n_hat * D;
     const uint8_t* tabg = a.tab + (int64_t)bh * a.tab_len;
 
-    for (int i = tid; i < a.words; i += PREFILL_THREADS) ob[i + 1] = a.obits[(int64_t)bh * a.words + i];
-    if (tid == 0) ob[0] = 0u;
+    const uint32_t* obg = a.obits + (int64_t)bh * (a.words + 1);          // zero word + bitmap of this head
+    if (OBLDS) for (int i = tid; i < a.words + 1; i += PREFILL_THREADS) ob_lds[i] = obg[i];
+    const uint32_t* ob = OBLDS ? ob_lds : obg;
     for (int i = tid; i < a.tab_len; i += PREFILL_THREADS) tab[i] = tabg[i];
     const int64_t pos = blockpos + 32 * wv + r32;
     const bool row_ok = (pos >= row0) && (pos < n);
@@ -1021,19 +1026,28 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
 }
 
 template <int D>
-static size_t prefill_bf16_smem(int words, int tab_len) {
-    return 2 * (size_t)DirectCfg<D>::TILE_BYTES + (size_t)(words + 1) * 4 + 192 * 4 + 8 * 4 +
+static size_t prefill_bf16_smem(int words, int tab_len, bool oblds) {
+    return 2 * (size_t)DirectCfg<D>::TILE_BYTES + (oblds ? (size_t)(words + 1) * 4 : 0) + 192 * 4 + 8 * 4 +
            (size_t)((tab_len + 7) & ~7) * 2 + (size_t)tab_len + 16;
 }
-
+// the bitmap goes to LDS when two workgroups still fit a CU's 160 KB with it
 template <int D>
-static hipError_t launch_prefill_bf16(const PrefillArgs& a, hipStream_t st) {
-    const size_t smem = prefill_bf16_smem<D>(a.words, a.tab_len);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_bf16_kernel<D>),
+static bool prefill_bf16_oblds(int words, int tab_len) {
+    return 2 * (prefill_bf16_smem<D>(words, tab_len, true) + 1024) <= 160 * 1024;
+}
+
+template <int D, bool OBLDS>
+static hipError_t launch_prefill_bf16_t(const PrefillArgs& a, hipStream_t st) {
+    const size_t smem = prefill_bf16_smem<D>(a.words, a.tab_len, OBLDS);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_bf16_kernel<D, OBLDS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_bf16_kernel<D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
+    hipLaunchKernelGGL((prefill_bf16_kernel<D, OBLDS>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
     return hipGetLastError();
+}
+template <int D>
+static hipError_t launch_prefill_bf16(const PrefillArgs& a, hipStream_t st) {
+    return prefill_bf16_oblds<D>(a.words, a.tab_len) ? launch_prefill_bf16_t<D, true>(a, st) : launch_prefill_bf16_t<D, false>(a, st);
 }
 
 template <typename T, int D>
@@ -1054,8 +1068,8 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
 }
 
 size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len) {
-    if (dtype == 0 && d == 128) return prefill_bf16_smem<128>(words, tab_len);
-    if (dtype == 0 && d == 64) return prefill_bf16_smem<64>(words, tab_len);
+    if (dtype == 0 && d == 128) return prefill_bf16_smem<128>(words, tab_len, prefill_bf16_oblds<128>(words, tab_len));
+    if (dtype == 0 && d == 64) return prefill_bf16_smem<64>(words, tab_len, prefill_bf16_oblds<64>(words, tab_len));
     if (dtype == 1 && d == 128) return prefill_smem_t<float, 128>(words, tab_len);
     return prefill_smem_t<float, 64>(words, tab_len);
 }
