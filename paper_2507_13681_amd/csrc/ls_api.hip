@@ -11,6 +11,8 @@
 #include "../../include/loopserve.h"
 #include "ls_internal.h"
 
+static_assert(ls::TOPB_MAX_LEN >= LS_MAX_N, "top-B kernel must cover the longest context");
+
 struct ls_ctx {
     int device;
     unsigned char* ws;

@@ -33,9 +33,11 @@ struct SelectArgs {
     float* accounted;         // may be null
 };
 
+constexpr int64_t TOPB_MAX_LEN = 262144;   // longest score row run_topb takes (its per-segment counts live in LDS)
+
 struct TopbArgs {
     const float* score;       // [BK][len]
-    int64_t len;
+    int64_t len;              // <= TOPB_MAX_LEN
     int budget;
     int32_t *keep_idx, *keep_cnt;
 };

@@ -504,11 +504,19 @@ __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
 
 // ---- top-B retention ------------------------------------------------------------------------------
 // grid (B*Hkv).  keep_idx [BK][budget] ascending; keep_cnt = min(budget, len).
-__global__ __launch_bounds__(1024) void topb_kernel(TopbArgs a) {
+// Radix select on the descending keys (four 8-bit digits, most significant first) finds the key K* of
+// the budget-th largest score; then one counting sweep and one writing sweep over 64-element segments
+// emit, in index order, every element above K* and the first few equal to it.
+constexpr int TOPB_THREADS = 1024;
+constexpr int TOPB_WAVES = TOPB_THREADS / 64;
+constexpr int TOPB_BATCH = 16;                          // independent loads in flight per lane
+constexpr int TOPB_MAX_SEG = (int)(TOPB_MAX_LEN / 64);
+
+__global__ __launch_bounds__(TOPB_THREADS) void topb_kernel(TopbArgs a) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel_prefix, sel_remaining;
-    __shared__ uint32_t wsum[16];
-    __shared__ uint32_t carry_gt, carry_eq;
+    __shared__ uint32_t wsum_gt[TOPB_WAVES], wsum_eq[TOPB_WAVES];
+    __shared__ uint32_t seg_gt[TOPB_MAX_SEG], seg_eq[TOPB_MAX_SEG];
     const int bk = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t len = a.len;
     const float* sc = a.score + (int64_t)bk * len;
@@ -516,10 +524,9 @@ __global__ __launch_bounds__(1024) void topb_kernel(TopbArgs a) {
     const int64_t keep = a.budget < len ? a.budget : len;
     if (tid == 0) a.keep_cnt[bk] = (int32_t)keep;
     if (keep == len) {
-        for (int64_t i = tid; i < len; i += 1024) out[i] = (int32_t)i;
+        for (int64_t i = tid; i < len; i += TOPB_THREADS) out[i] = (int32_t)i;
         return;
     }
-    // radix select on descending keys: find the key value K* of the keep-th element
     if (tid == 0) { sel_prefix = 0u; sel_remaining = (uint32_t)keep; }
     __syncthreads();
     for (int pass = 3; pass >= 0; --pass) {
@@ -528,45 +535,109 @@ __global__ __launch_bounds__(1024) void topb_kernel(TopbArgs a) {
         __syncthreads();
         const uint32_t prefix = sel_prefix;
         const uint32_t himask = pass == 3 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int64_t i = tid; i < len; i += 1024) {
-            const uint32_t key = desc_key(sc[i]);
-            if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        for (int64_t i0 = tid; i0 < len; i0 += TOPB_BATCH * TOPB_THREADS) {
+            uint32_t kb[TOPB_BATCH];
+#pragma unroll
+            for (int j = 0; j < TOPB_BATCH; ++j) {
+                const int64_t i = i0 + j * TOPB_THREADS;
+                kb[j] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int j = 0; j < TOPB_BATCH; ++j) {
+                // scores of one head crowd into few digits: lanes with the same digit add once, through their first lane
+                const bool on = i0 + j * TOPB_THREADS < len && (kb[j] & himask) == prefix;
+                const uint32_t digit = (kb[j] >> shift) & 255u;
+                uint64_t peers = __ballot(on);
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const bool bit = (digit >> b) & 1u;
+                    const uint64_t m = __ballot(bit);
+                    peers &= bit ? m : ~m;
+                }
+                if (on && __ffsll((unsigned long long)peers) - 1 == lane) atomicAdd(&hist[digit], (uint32_t)__popcll(peers));
+            }
         }
         __syncthreads();
-        if (tid == 0) {
-            uint32_t rem = sel_remaining, d = 0;
-            for (; d < 256; ++d) { if (hist[d] >= rem) break; rem -= hist[d]; }
-            sel_prefix = prefix | (d << shift);
-            sel_remaining = rem;                       // how many elements equal to the prefix so far are still needed
+        if (wv == 0) {
+            // digit whose running count first reaches what is still needed: four digits per lane, scanned over the wave
+            const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            const uint32_t s = h0 + h1 + h2 + h3;
+            uint32_t inc = s;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
+            const uint32_t rem = sel_remaining;
+            const uint64_t reach = __ballot(inc >= rem);   // never empty: the prefix holds at least rem elements
+            if (__ffsll((unsigned long long)reach) - 1 == lane) {
+                uint32_t r = rem - (inc - s), d = 4u * lane;
+                if (h0 < r) { r -= h0; ++d; if (h1 < r) { r -= h1; ++d; if (h2 < r) { r -= h2; ++d; } } }
+                sel_prefix = prefix | (d << shift);
+                sel_remaining = r;                     // elements equal to the prefix so far that are still needed
+            }
         }
         __syncthreads();
     }
     const uint32_t kstar = sel_prefix;                 // smaller key = larger score
     const uint32_t need_eq = sel_remaining;            // elements with key == kstar to keep (smallest indices)
-    if (tid == 0) { carry_gt = 0u; carry_eq = 0u; }
-    __syncthreads();
-    // ordered pass: position = (#kept before me); kept = key < kstar, or key == kstar among the first need_eq
-    for (int64_t c0 = 0; c0 < len; c0 += 1024) {
-        const int64_t i = c0 + tid;
-        const uint32_t key = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
-        const uint32_t gt = (i < len && key < kstar) ? 1u : 0u;
-        const uint32_t eq = (i < len && key == kstar) ? 1u : 0u;
-        uint32_t v = gt | (eq << 16);                  // both counts in one scan (chunk <= 1024 < 65536)
-        uint32_t inc = v;
+    const int64_t nseg = (len + 63) >> 6;
+    // counting sweep: per 64-element segment, how many lie above K* and how many equal it
+    for (int64_t s0 = wv; s0 < nseg; s0 += TOPB_BATCH * TOPB_WAVES) {
+        uint32_t kb[TOPB_BATCH];
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
-        if (lane == 63) wsum[wv] = inc;
+        for (int j = 0; j < TOPB_BATCH; ++j) {
+            const int64_t i = (s0 + j * TOPB_WAVES) * 64 + lane;
+            kb[j] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int j = 0; j < TOPB_BATCH; ++j) {
+            const int64_t s = s0 + j * TOPB_WAVES, i = s * 64 + lane;
+            const uint64_t gt = __ballot(i < len && kb[j] < kstar), eq = __ballot(i < len && kb[j] == kstar);
+            if (s < nseg && lane == 0) { seg_gt[s] = (uint32_t)__popcll(gt); seg_eq[s] = (uint32_t)__popcll(eq); }
+        }
+    }
+    __syncthreads();
+    {   // exclusive scan of the segment counts, in place: a run of consecutive segments per thread
+        const int per = (int)((nseg + TOPB_THREADS - 1) / TOPB_THREADS);
+        const int64_t b = (int64_t)tid * per, e = b + per < nseg ? b + per : nseg;
+        uint32_t tg = 0, te = 0;
+        for (int64_t s = b; s < e; ++s) { tg += seg_gt[s]; te += seg_eq[s]; }
+        uint32_t ig = tg, ie = te;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t ug = __shfl_up(ig, off, 64), ue = __shfl_up(ie, off, 64);
+            if (lane >= off) { ig += ug; ie += ue; }
+        }
+        if (lane == 63) { wsum_gt[wv] = ig; wsum_eq[wv] = ie; }
         __syncthreads();
-        uint32_t pre = 0;
-        for (int w = 0; w < wv; ++w) pre += wsum[w];
-        const uint32_t ex = pre + inc - v;
-        const uint32_t gt_before = carry_gt + (ex & 0xFFFFu), eq_before = carry_eq + (ex >> 16);
-        const uint32_t eq_kept_before = eq_before < need_eq ? eq_before : need_eq;
-        const bool kept = gt || (eq && eq_before < need_eq);
-        if (kept) out[gt_before + eq_kept_before] = (int32_t)i;
-        __syncthreads();
-        if (tid == 1023) { const uint32_t tot = pre + inc; carry_gt += tot & 0xFFFFu; carry_eq += tot >> 16; }
-        __syncthreads();
+        uint32_t pg = ig - tg, pe = ie - te;
+        for (int w = 0; w < wv; ++w) { pg += wsum_gt[w]; pe += wsum_eq[w]; }
+        for (int64_t s = b; s < e; ++s) {
+            const uint32_t g = seg_gt[s], q = seg_eq[s];
+            seg_gt[s] = pg; seg_eq[s] = pe;
+            pg += g; pe += q;
+        }
+    }
+    __syncthreads();
+    // writing sweep: slot = kept elements before me; kept = above K*, or equal to it among the first need_eq
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (int64_t s0 = wv; s0 < nseg; s0 += TOPB_BATCH * TOPB_WAVES) {
+        uint32_t kb[TOPB_BATCH];
+#pragma unroll
+        for (int j = 0; j < TOPB_BATCH; ++j) {
+            const int64_t i = (s0 + j * TOPB_WAVES) * 64 + lane;
+            kb[j] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int j = 0; j < TOPB_BATCH; ++j) {
+            const int64_t s = s0 + j * TOPB_WAVES, i = s * 64 + lane;
+            const bool gt = i < len && kb[j] < kstar, eq = i < len && kb[j] == kstar;
+            const uint64_t gtm = __ballot(gt), eqm = __ballot(eq);
+            if (s < nseg) {
+                const uint32_t gt_before = seg_gt[s] + (uint32_t)__popcll(gtm & below);
+                const uint32_t eq_before = seg_eq[s] + (uint32_t)__popcll(eqm & below);
+                const uint32_t eq_kept_before = eq_before < need_eq ? eq_before : need_eq;
+                if (gt || (eq && eq_before < need_eq)) out[gt_before + eq_kept_before] = (int32_t)i;
+            }
+        }
     }
 }
 
@@ -602,7 +673,8 @@ hipError_t run_select(const SelectArgs& a, hipStream_t st) {
 }
 
 hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st) {
-    hipLaunchKernelGGL(topb_kernel, dim3(BK), dim3(1024), 0, st, a);
+    if (a.len < 1 || a.len > TOPB_MAX_LEN || a.budget < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(topb_kernel, dim3(BK), dim3(TOPB_THREADS), 0, st, a);
     return hipGetLastError();
 }
 
