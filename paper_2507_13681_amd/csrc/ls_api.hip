@@ -147,7 +147,6 @@ int ls_score(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_p
     if (!aligned16(q_win) || !aligned16(k) || !aligned16(vert) || !aligned16(slash) || !aligned16(vmax) ||
         !aligned16(smax) || (q_pos && (reinterpret_cast<uintptr_t>(q_pos) & 7u)))
         return fail(c, LS_EINVAL, "ls_score: misaligned tensor");
-    if (ls::score_lines_smem(s->w) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_score: w too large for LDS");
     ls::ScoreArgs a{};
     a.q = q_win; a.k = k; a.q_pos = q_pos; a.n = s->n; a.w = s->w; a.G = s->Hq / s->Hkv; a.Hq = s->Hq;
     a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
@@ -159,6 +158,7 @@ int ls_score(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_p
     a.vert = vert; a.slash = slash; a.vmax = vmax; a.smax = smax; a.total = total; a.gscore = nullptr;
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_score: hipSetDevice failed");
     const int mode = (q_pos == nullptr && s->w <= 128) ? 0 : 1;
+    if (ls::score_lines_smem(s->w, s->dtype, s->d, mode) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_score: w too large for LDS");
     const hipError_t e = ls::run_score(a, s->dtype, s->d, mode, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_score: %s", hipGetErrorString(e));
     return LS_OK;
@@ -261,6 +261,7 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
     if (!c) return LS_EINVAL;
     if (const char* m = check_shape(s, false, true, false)) return fail(c, LS_ESHAPE, "ls_kv_compress: %s", m);
     if (budget <= 0) return fail(c, LS_ESHAPE, "ls_kv_compress: budget must be positive");
+    if (ls::score_lines_smem(s->w, s->dtype, s->d, 2) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_kv_compress: w too large for LDS");
     if (!q_obs || !k || !keep_idx || !keep_cnt || (v_out && !v)) return fail(c, LS_EINVAL, "ls_kv_compress: NULL tensor");
     if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
         return fail(c, LS_EINVAL, "ls_kv_compress: misaligned tensor");

@@ -95,6 +95,10 @@ __device__ __forceinline__ void dma16(const unsigned char* gptr, uint32_t lds) {
 }
 __device__ __forceinline__ void wait_transfers() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for the wave's outstanding global
+// loads and stores; a kernel whose waves exchange data through LDS alone need not stall on a store's round trip.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // LDS transpose read of a bf16 tile stored row-major: in a block of 16 lanes, lane s addresses 4
 // consecutive 16-bit values and lane L receives value L % 4 of the lanes L/4, L/4+4, L/4+8, L/4+12.
 // Two reads (rows r .. and r + 8 ..) give a lane the eight contraction-index values of a fragment.

@@ -100,7 +100,7 @@ struct DecodeArgs {
 hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st);
 hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st);
 size_t decode_smem_bytes(int d, int G);
-size_t score_lines_smem(int w);
+size_t score_lines_smem(int w, int dtype, int d, int mode);
 hipError_t run_select(const SelectArgs& a, hipStream_t st);
 hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st);
 hipError_t run_gather_rows(const void* src, void* dst, const int32_t* keep_idx, const int32_t* keep_cnt,

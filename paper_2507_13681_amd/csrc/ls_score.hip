@@ -49,42 +49,113 @@ __device__ __forceinline__ void load_q_frags(Frag<T> (&qf)[D / 16], const T* Qh,
     }
 }
 
+// ---- the window's queries of one head, staged in LDS ---------------------------------------------
+// Every workgroup of a KV head needs the same few KB of Q for each of its G heads; read straight from
+// global memory by each wave (as the K fragments are) those reads all hit the same handful of L2 lines and
+// took half of both passes.  One copy per workgroup and head goes through LDS instead: row-major, the
+// 8-element fragment units of a row XOR-swizzled with the row so that the 16 rows one fragment read touches
+// fall into different banks.  The next head's units are fetched into registers while the current head is
+// multiplied.
+template <typename T, int D>
+struct QStage {
+    static constexpr int FB = 8 * Elem<T>::bytes;         // bytes of one fragment unit (8 elements)
+    static constexpr int UPR = D / 8;                     // units per row
+    static constexpr int RBYTES = D * Elem<T>::bytes;
+    static constexpr int PF = 4;                          // units per thread held in registers
+    struct Unit { f32x4 v[FB / 16]; };
+    __device__ static void fetch(Unit (&u)[PF], const T* Qh, int w, int wpad, int tid) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            const int i = tid + SCORE_THREADS * j, row = i / UPR, uu = i % UPR;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int h = 0; h < FB / 16; ++h)
+                u[j].v[h] = (i < wpad * UPR && row < w) ? reinterpret_cast<const f32x4*>(Qh + (int64_t)row * D + 8 * uu)[h] : z;
+        }
+    }
+    __device__ static unsigned char* slot(unsigned char* qs, int row, int uu) {
+        return qs + row * RBYTES + FB * (uu ^ (row & (UPR - 1)));
+    }
+    // registers -> LDS; rows beyond the register budget (long windows) are copied directly
+    __device__ static void commit(unsigned char* qs, const Unit (&u)[PF], const T* Qh, int w, int wpad, int tid) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            const int i = tid + SCORE_THREADS * j, row = i / UPR, uu = i % UPR;
+            if (i < wpad * UPR) {
+#pragma unroll
+                for (int h = 0; h < FB / 16; ++h) reinterpret_cast<f32x4*>(slot(qs, row, uu))[h] = u[j].v[h];
+            }
+        }
+        for (int i = tid + SCORE_THREADS * PF; i < wpad * UPR; i += SCORE_THREADS) {
+            const int row = i / UPR, uu = i % UPR;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int h = 0; h < FB / 16; ++h)
+                reinterpret_cast<f32x4*>(slot(qs, row, uu))[h] = row < w ? reinterpret_cast<const f32x4*>(Qh + (int64_t)row * D + 8 * uu)[h] : z;
+        }
+    }
+    __device__ static void frags(Frag<T> (&qf)[D / 16], const unsigned char* qs, int row, int g) {
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) load_frag(qf[c], qs + row * RBYTES + FB * ((2 * c + g) ^ (row & (UPR - 1))));
+    }
+};
+
 // ---- pass 1: per (row, key block) max and sum of exp2 -----------------------------------------
-// grid (nkb, B*Hkv).  part[(bh*w + row)*nkb + kb] = {max, sum}.
+// grid (nkb, B*Hkv), dynamic LDS: the staged Q of one head.  part[(bh*w + row)*nkb + kb] = {max, sum}.
 template <typename T, int D>
 __global__ __launch_bounds__(SCORE_THREADS) void stats_kernel(ScoreArgs a) {
-    __shared__ float red[4][32][2];
+    using QS = QStage<T, D>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* qs = smem;                              // [wpad][D] staged queries
+    __shared__ float red[2][4][32][2];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, r32 = lane & 31, g = lane >> 5;
     const int kb = blockIdx.x, bk = blockIdx.y;
     const int b = bk / a.Hkv, kvh = bk % a.Hkv;
     const int64_t n = a.n;
     const T* Kg = reinterpret_cast<const T*>(a.k) + (int64_t)bk * n * D;
     const int64_t key0 = (int64_t)kb * SB + 32 * wv;
+    const int wpad = ((a.w + 31) / 32) * 32;
+    const int rgs = wpad / 32;
+    const int bh0 = b * a.Hq + kvh * a.G;
+    const T* Q0 = reinterpret_cast<const T*>(a.q) + (int64_t)bh0 * a.w * D;
+    typename QS::Unit qu[QS::PF];
+    QS::fetch(qu, Q0, a.w, wpad, tid);
     Frag<T> kf[D / 16];
     load_k_frags<T, D>(kf, Kg, key0 + r32, n, g);
-    const int rgs = (a.w + 31) / 32;
+    // every key of the block is visible to every row of a contiguous window: no masks (all but the last blocks)
+    const bool open = a.q_pos == nullptr && (int64_t)kb * SB + SB - 1 <= n - a.w;
+    int it = 0;
     for (int gq = 0; gq < a.G; ++gq) {
-        const int bh = b * a.Hq + kvh * a.G + gq;
-        const T* Qh = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.w * D;
-        for (int rg = 0; rg < rgs; ++rg) {
+        const int bh = bh0 + gq;
+        const T* Qh = Q0 + (int64_t)gq * a.w * D;
+        lds_barrier();                                     // the previous head's fragments have been read
+        QS::commit(qs, qu, Qh, a.w, wpad, tid);
+        lds_barrier();
+        if (gq + 1 < a.G) QS::fetch(qu, Qh + (int64_t)a.w * D, a.w, wpad, tid);
+        for (int rg = 0; rg < rgs; ++rg, ++it) {
             const int row = 32 * rg + r32;
             Frag<T> qf[D / 16];
-            load_q_frags<T, D>(qf, Qh, row, a.w, g);
+            QS::frags(qf, qs, row, g);
             f32x16 s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
             for (int c = 0; c < D / 16; ++c) mma(s, kf[c], qf[c]);   // s[r] = <k_{8(r/4)+4g+r%4}, q_row>
-            int64_t p = (row < a.w) ? (a.q_pos ? a.q_pos[row] : n - a.w + row) : -1;
-            if (p > n - 1) p = n - 1;                  // positions outside the context are clipped
-            if (p < -1) p = -1;
             float mx = -INFINITY;
+            if (open && row < a.w) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t key = key0 + 8 * (r >> 2) + 4 * g + (r & 3);
-                const float x = (key <= p) ? s[r] * a.scale_log2e : -INFINITY;
-                s[r] = x;
-                mx = fmaxf(mx, x);
+                for (int r = 0; r < 16; ++r) { s[r] *= a.scale_log2e; mx = fmaxf(mx, s[r]); }
+            } else {
+                int64_t p = (row < a.w) ? (a.q_pos ? a.q_pos[row] : n - a.w + row) : -1;
+                if (p > n - 1) p = n - 1;                  // positions outside the context are clipped
+                int64_t lim64 = p - key0 - 4 * g;          // register r holds key key0 + 4g + 8(r/4) + r%4
+                const int lim = lim64 < -1 ? -1 : (lim64 > 64 ? 64 : (int)lim64);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float x = (8 * (r >> 2) + (r & 3) <= lim) ? s[r] * a.scale_log2e : -INFINITY;
+                    s[r] = x;
+                    mx = fmaxf(mx, x);
+                }
             }
             mx = fmaxf(mx, xor32(mx));
             const float ms = (mx == -INFINITY) ? 0.f : mx;
@@ -92,17 +163,17 @@ __global__ __launch_bounds__(SCORE_THREADS) void stats_kernel(ScoreArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum += fast_exp2(s[r] - ms);
             sum += xor32(sum);
-            __syncthreads();
-            if (g == 0) { red[wv][r32][0] = mx; red[wv][r32][1] = sum; }
-            __syncthreads();
+            float (*rb)[32][2] = red[it & 1];              // two buffers: one barrier per iteration
+            if (g == 0) { rb[wv][r32][0] = mx; rb[wv][r32][1] = sum; }
+            lds_barrier();
             if (wv == 0 && g == 0 && row < a.w) {
                 float M = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) M = fmaxf(M, red[i][r32][0]);
+                for (int i = 0; i < 4; ++i) M = fmaxf(M, rb[i][r32][0]);
                 const float Ms = (M == -INFINITY) ? 0.f : M;
                 float L = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) L += red[i][r32][1] * fast_exp2(red[i][r32][0] - Ms);
+                for (int i = 0; i < 4; ++i) L += rb[i][r32][1] * fast_exp2(rb[i][r32][0] - Ms);
                 float* dst = a.part + (((int64_t)bh * a.w + row) * a.nkb + kb) * 2;
                 dst[0] = M; dst[1] = L;
             }
@@ -133,48 +204,64 @@ __global__ __launch_bounds__(256) void merge_kernel(ScoreArgs a, int rows) {
 }
 
 // ---- pass 2: line sums ------------------------------------------------------------------------
-// grid (nkb, B*Hkv), dynamic LDS: A slab [w_pad][SB + 1] floats + row stats [w_pad][2] + positions.
+// grid (nkb, B*Hkv), dynamic LDS: A slab [wpad][SB + 1] floats + row stats [wpad][2] + row limits [wpad] +
+// the staged Q of one head.
 // MODE 0: vert/vmax per head + diagonal partials (contiguous window, q_pos == NULL)
 // MODE 1: vert/vmax per head + diagonals through atomics (explicit q_pos)
 // MODE 2: column sums only, summed over the G heads of the KV head (retention score)
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
+    using QS = QStage<T, D>;
     extern __shared__ __align__(16) unsigned char smem[];
     const int wpad = ((a.w + 31) / 32) * 32;
-    float* slab = reinterpret_cast<float*>(smem);                  // [wpad][SB+1]
-    float* rst = slab + (size_t)wpad * (SB + 1);                   // [wpad][2]
-    int64_t* qp = reinterpret_cast<int64_t*>(rst + 2 * wpad);      // [wpad]
+    float* slab = reinterpret_cast<float*>(smem);                  // [wpad][SB+1], MODE 0 only
+    float* rst = slab + (MODE == 0 ? (size_t)wpad * (SB + 1) : 0); // [wpad][2], 16-byte aligned (wpad % 32 == 0)
+    int32_t* ql = reinterpret_cast<int32_t*>(rst + 2 * wpad);      // [wpad] last visible key of a row, relative to the block
+    unsigned char* qs = reinterpret_cast<unsigned char*>(ql + wpad);   // [wpad][D] staged queries
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, r32 = lane & 31, g = lane >> 5;
     const int kb = blockIdx.x, bk = blockIdx.y;
     const int b = bk / a.Hkv, kvh = bk % a.Hkv;
     const int64_t n = a.n;
     const T* Kg = reinterpret_cast<const T*>(a.k) + (int64_t)bk * n * D;
-    const int64_t key0 = (int64_t)kb * SB + 32 * wv;
-    const int64_t mykey = key0 + r32;
+    const int64_t blk0 = (int64_t)kb * SB;
+    const int64_t mykey = blk0 + 32 * wv + r32;
+    const int klocal = 32 * wv + r32;
+    const int bh0 = b * a.Hq + kvh * a.G;
+    const T* Q0 = reinterpret_cast<const T*>(a.q) + (int64_t)bh0 * a.w * D;
+    typename QS::Unit qu[QS::PF];
+    QS::fetch(qu, Q0, a.w, wpad, tid);
+    float rs_m = tid < a.w ? a.rowstat[2 * ((int64_t)bh0 * a.w + tid)] : 0.f;        // wpad <= 256 = one row per thread
+    float rs_il = tid < a.w ? a.rowstat[2 * ((int64_t)bh0 * a.w + tid) + 1] : 0.f;
     Frag<T> kf[D / 16];
     load_k_frags<T, D>(kf, Kg, mykey, n, g);
     for (int i = tid; i < wpad; i += SCORE_THREADS) {
         int64_t p = (i < a.w) ? (a.q_pos ? a.q_pos[i] : n - a.w + i) : -1;
         if (p > n - 1) p = n - 1;                          // positions outside the context are clipped
-        if (p < -1) p = -1;
-        qp[i] = p;
+        const int64_t rel = p - blk0;                      // key klocal of the block is visible to row i iff klocal <= rel
+        ql[i] = rel < -1 ? -1 : (rel > SB ? SB : (int32_t)rel);
     }
+    // every key of the block is visible to every row of a contiguous window (all but the last blocks)
+    const bool open = a.q_pos == nullptr && blk0 + SB - 1 <= n - a.w;
     const int rgs = wpad / 32;
     float gsum = 0.f;                                              // MODE 2 accumulator over heads
     for (int gq = 0; gq < a.G; ++gq) {
-        const int bh = b * a.Hq + kvh * a.G + gq;
-        const T* Qh = reinterpret_cast<const T*>(a.q) + (int64_t)bh * a.w * D;
-        __syncthreads();                                           // slab / rst free again
-        for (int i = tid; i < wpad; i += SCORE_THREADS) {
-            const bool ok = i < a.w;
-            rst[2 * i] = ok ? a.rowstat[2 * ((int64_t)bh * a.w + i)] : 0.f;
-            rst[2 * i + 1] = ok ? a.rowstat[2 * ((int64_t)bh * a.w + i) + 1] : 0.f;
+        const int bh = bh0 + gq;
+        const T* Qh = Q0 + (int64_t)gq * a.w * D;
+        lds_barrier();                                             // slab / rst / staged Q free again
+        if (tid < wpad) { rst[2 * tid] = rs_m; rst[2 * tid + 1] = rs_il; }
+        QS::commit(qs, qu, Qh, a.w, wpad, tid);
+        lds_barrier();
+        // the next head's row statistics and queries are requested before this head's results are stored: a load
+        // issued after a store would not return before the store's round trip has ended (one in-order counter)
+        if (gq + 1 < a.G) {
+            rs_m = tid < a.w ? a.rowstat[2 * ((int64_t)(bh + 1) * a.w + tid)] : 0.f;
+            rs_il = tid < a.w ? a.rowstat[2 * ((int64_t)(bh + 1) * a.w + tid) + 1] : 0.f;
+            QS::fetch(qu, Qh + (int64_t)a.w * D, a.w, wpad, tid);
         }
-        __syncthreads();
         float vsum = 0.f, vmx = 0.f;
         for (int rg = 0; rg < rgs; ++rg) {
             Frag<T> qf[D / 16];
-            load_q_frags<T, D>(qf, Qh, 32 * rg + r32, a.w, g);
+            QS::frags(qf, qs, 32 * rg + r32, g);
             f32x16 s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -182,18 +269,33 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
             for (int c = 0; c < D / 16; ++c) mma(s, qf[c], kf[c]);   // s[r] = <q_{8(r/4)+4g+r%4}, k_lane>
             float ps = 0.f, pm = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = 32 * rg + 8 * (r >> 2) + 4 * g + (r & 3);
-                const float m = rst[2 * row], il = rst[2 * row + 1];
-                const float p = (mykey <= qp[row]) ? fast_exp2(s[r] * a.scale_log2e - m) * il : 0.f;
-                ps += p;
-                pm = fmaxf(pm, p);
-                if (MODE == 0) slab[row * (SB + 1) + 32 * wv + r32] = p;
-                if (MODE == 1 && p > 0.f) {
-                    const int64_t o = qp[row] - mykey;
-                    atomicAdd(a.slash + (int64_t)bh * n + o, p);
-                    atomicMax(reinterpret_cast<unsigned int*>(a.smax + (int64_t)bh * n + o),
-                              __builtin_bit_cast(unsigned int, p));
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int row0 = 32 * rg + 8 * q4 + 4 * g;         // registers 4*q4 .. 4*q4+3 hold rows row0 .. row0+3
+                const f32x4 st0 = reinterpret_cast<const f32x4*>(rst + 2 * row0)[0];     // m, 1/l of rows row0, row0+1
+                const f32x4 st1 = reinterpret_cast<const f32x4*>(rst + 2 * row0)[1];     // ... row0+2, row0+3
+                const float mm[4] = {st0.x, st0.z, st1.x, st1.z}, il[4] = {st0.y, st0.w, st1.y, st1.w};
+                int32_t lim[4] = {SB, SB, SB, SB};
+                if (!open) {
+                    typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+                    const i32x4 l4 = *reinterpret_cast<const i32x4*>(ql + row0);
+                    lim[0] = l4.x; lim[1] = l4.y; lim[2] = l4.z; lim[3] = l4.w;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * q4 + e, row = row0 + e;
+                    float p = fast_exp2(s[r] * a.scale_log2e - mm[e]) * il[e];
+                    if (!open) p = (klocal <= lim[e]) ? p : 0.f;
+                    ps += p;
+                    pm = fmaxf(pm, p);
+                    if (MODE == 0) slab[row * (SB + 1) + klocal] = p;
+                    if (MODE == 1 && p > 0.f) {
+                        int64_t pr = a.q_pos ? a.q_pos[row] : n - a.w + row;
+                        if (pr > n - 1) pr = n - 1;
+                        const int64_t o = pr - mykey;
+                        atomicAdd(a.slash + (int64_t)bh * n + o, p);
+                        atomicMax(reinterpret_cast<unsigned int*>(a.smax + (int64_t)bh * n + o),
+                                  __builtin_bit_cast(unsigned int, p));
+                    }
                 }
             }
             ps += xor32(ps);
@@ -207,19 +309,26 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
             a.vmax[(int64_t)bh * n + mykey] = vmx;
         }
         if (MODE == 0) {
-            __syncthreads();
+            lds_barrier();
             // thread j owns diagonal o = omin + j of this slab; key_local = t + (SB-1) - j for row t
-            const int64_t omin = n - a.w - ((int64_t)kb * SB + SB - 1);
+            const int64_t omin = n - a.w - (blk0 + SB - 1);
             for (int j = tid; j < SB - 1 + a.w; j += SCORE_THREADS) {
                 const int64_t o = omin + j;
                 if (o < 0) continue;
                 float ssum = 0.f, smx = 0.f;
                 const int t0 = j - (SB - 1) > 0 ? j - (SB - 1) : 0;
                 const int t1 = j < a.w - 1 ? j : a.w - 1;
-                for (int t = t0; t <= t1; ++t) {
-                    const float p = slab[t * (SB + 1) + t + (SB - 1) - j];
-                    ssum += p;
-                    smx = fmaxf(smx, p);
+                // rows in ascending order, eight reads in flight; a row outside t0..t1 adds an exact zero
+                const float* dp = slab + (SB - 1) - j;             // row t of this diagonal sits at dp[t * (SB + 2)]
+                for (int tb = t0 & ~7; tb <= t1; tb += 8) {
+                    float p8[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int t = tb + e;
+                        p8[e] = (t >= t0 && t <= t1) ? dp[t * (SB + 2)] : 0.f;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) { ssum += p8[e]; smx = fmaxf(smx, p8[e]); }
                 }
                 float* dst = a.spart + (((int64_t)(kb & 1) * a.BH + bh) * n + o) * 2;
                 dst[0] = ssum; dst[1] = smx;
@@ -285,12 +394,15 @@ __global__ void fill_zero_kernel(float* p, int64_t count) {
 template <typename T, int D>
 static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.nkb, a.B * a.Hkv);
-    hipLaunchKernelGGL((stats_kernel<T, D>), grid, dim3(SCORE_THREADS), 0, st, a);
+    const int wpad = ((a.w + 31) / 32) * 32;
+    const size_t qbytes = (size_t)wpad * D * Elem<T>::bytes;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_kernel<T, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)qbytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((stats_kernel<T, D>), grid, dim3(SCORE_THREADS), qbytes, st, a);
     const int rows = a.BH * a.w;
     hipLaunchKernelGGL(merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, a, rows);
-    const int wpad = ((a.w + 31) / 32) * 32;
-    const size_t smem = (size_t)wpad * (SB + 1) * 4 + (size_t)wpad * 8 + (size_t)wpad * 8;
-    hipError_t e;
+    const size_t smem = (mode == 0 ? (size_t)wpad * (SB + 1) * 4 : 0) + (size_t)wpad * 8 + (size_t)wpad * 4 + qbytes;
     if (mode == 0) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -323,9 +435,10 @@ hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t
     return hipErrorInvalidValue;
 }
 
-size_t score_lines_smem(int w) {
+// dynamic LDS of lines_kernel (the larger of the two passes)
+size_t score_lines_smem(int w, int dtype, int d, int mode) {
     const int wpad = ((w + 31) / 32) * 32;
-    return (size_t)wpad * (SB + 1) * 4 + (size_t)wpad * 16;
+    return (mode == 0 ? (size_t)wpad * (SB + 1) * 4 : 0) + (size_t)wpad * 12 + (size_t)wpad * d * (dtype == 0 ? 2 : 4);
 }
 
 }  // namespace ls
