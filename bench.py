@@ -146,11 +146,15 @@ def main():
         cctx.ls_kv_compress(cshape, args.budget, qobs, kd, None, keep_idx, keep_cnt)
 
     def step():
+        # compress is issued once the scoring kernels (which fill the chip themselves) are queued, so that it runs
+        # beside the selection kernels; measured: beside score + select 2.80 ms per step, after everything 2.86,
+        # beside select only 2.73, beside the attention kernel 3.40
         main = torch.cuda.current_stream()
+        f_score()
         side.wait_stream(main)
         with torch.cuda.stream(side):
             f_compress()
-        f_score(); f_select(); f_prefill()
+        f_select(); f_prefill()
         main.wait_stream(side)
 
     def timed(fn, reps):

@@ -26,6 +26,8 @@ def _score_close(gpu, ref, w):
     (1, 8, 2, 1000, 64, 128, "bf16"),
     (1, 2, 2, 129, 128, 128, "f32"),      # window almost the whole context
     (1, 2, 1, 40, 40, 64, "bf16"),        # first turn: every row scored, single key block
+    (1, 4, 2, 600, 100, 128, "bf16"),     # window longer than the staged-query register budget, ragged rows
+    (1, 2, 1, 700, 256, 128, "f32"),      # longest window: largest LDS footprint, diagonals through atomics
 ])
 def test_score_matches_oracle(oracle, B, Hq, Hkv, n, w, d, dtype):
     q, k, v = inputs.make_plain(B, Hq, Hkv, n, w, d, dtype=dtype, seed=n + w, q_scale=2.0)
