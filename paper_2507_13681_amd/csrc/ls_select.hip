@@ -163,13 +163,21 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
         for (int i = tid; i < SORT_SEG; i += SORT_THREADS) other[i] = i < qc ? a.skey0[lbase + qb + i] : 0xFFFFFFFFu;
         __syncthreads();
         const uint32_t incl = q < seg ? 1u : 0u;           // equal keys of an earlier segment go first
+        // number of i in [0, qc) with other[i] < key + incl (as 64-bit: key may be 0xFFFFFFFF).  The segment is
+        // padded to its full power-of-two length with the largest key, so the search has a fixed number of steps
+        // and the MERGE_PER searches of a thread advance together: their LDS reads are in flight at the same time.
+        int lo[MERGE_PER];
+#pragma unroll
+        for (int j = 0; j < MERGE_PER; ++j) lo[j] = 0;
+        for (int step = SORT_SEG / 2; step >= 1; step >>= 1) {
+#pragma unroll
+            for (int j = 0; j < MERGE_PER; ++j)
+                if ((uint64_t)other[lo[j] + step - 1] < (uint64_t)key[j] + incl) lo[j] += step;
+        }
 #pragma unroll
         for (int j = 0; j < MERGE_PER; ++j) {
-            // number of i in [0, qc) with other[i] < key + incl (as 64-bit: key may be 0xFFFFFFFF)
-            const uint64_t lim = (uint64_t)key[j] + incl;
-            int lo = 0, hi = qc;
-            while (lo < hi) { const int mid = (lo + hi) >> 1; if ((uint64_t)other[mid] < lim) lo = mid + 1; else hi = mid; }
-            rank[j] += (uint32_t)lo;
+            int r = lo[j] + ((uint64_t)other[lo[j]] < (uint64_t)key[j] + incl ? 1 : 0);
+            rank[j] += (uint32_t)(r < qc ? r : qc);
         }
     }
     const float* mx = (list == 0 ? a.smax : a.vmax) + (int64_t)bh * n;
