@@ -103,7 +103,7 @@ struct QStage {
 // ---- pass 1: per (row, key block) max and sum of exp2 -----------------------------------------
 // grid (nkb, B*Hkv), dynamic LDS: the staged Q of one head.  part[(bh*w + row)*nkb + kb] = {max, sum}.
 template <typename T, int D>
-__global__ __launch_bounds__(SCORE_THREADS) void stats_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(SCORE_THREADS, (Elem<T>::bytes == 2 ? 4 : 1)) void stats_kernel(ScoreArgs a) {
     using QS = QStage<T, D>;
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* qs = smem;                              // [wpad][D] staged queries
