@@ -92,7 +92,8 @@ size_t ws_prefill(const ls_shape* s) {
            up(8 * items * 4) + 2 * up(8 * 4);
 }
 size_t ws_compress(const ls_shape* s) {
-    return ws_score(s, false) + up((size_t)s->B * s->Hkv * (size_t)s->n * 4);
+    return ws_score(s, false) + up((size_t)s->B * s->Hkv * (size_t)s->n * 4) +
+           up(ls::topb_scratch_words(s->B * s->Hkv, s->n) * 4);
 }
 
 }  // namespace
@@ -273,6 +274,7 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
     a.part = bp.take<float>((size_t)a.BH * a.w * a.nkb * 2);
     a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
     a.gscore = bp.take<float>((size_t)BK * (size_t)a.n);
+    uint32_t* tb_scratch = bp.take<uint32_t>(ls::topb_scratch_words(BK, s->n));
     if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_kv_compress: workspace of %zu bytes is too small", c->ws_bytes);
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress: hipSetDevice failed");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -280,7 +282,7 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(score): %s", hipGetErrorString(e));
     ls::TopbArgs t{};
     t.score = a.gscore; t.len = s->n; t.budget = budget; t.keep_idx = keep_idx; t.keep_cnt = keep_cnt;
-    e = ls::run_topb(t, BK, st);
+    e = ls::run_topb(t, BK, tb_scratch, st);
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(topb): %s", hipGetErrorString(e));
     const int row_bytes = s->d * (s->dtype == LS_BF16 ? 2 : 4);
     if (k_out) {

@@ -33,13 +33,16 @@ struct SelectArgs {
     float* accounted;         // may be null
 };
 
-constexpr int64_t TOPB_MAX_LEN = 262144;   // longest score row run_topb takes (its per-segment counts live in LDS)
+constexpr int64_t TOPB_MAX_LEN = 262144;   // longest score row run_topb takes
 
 struct TopbArgs {
     const float* score;       // [BK][len]
     int64_t len;              // <= TOPB_MAX_LEN
     int budget;
     int32_t *keep_idx, *keep_cnt;
+    // filled in by run_topb from its scratch block
+    int chunks;
+    uint32_t *hist, *state, *cnt;
 };
 
 struct PlanArgs {
@@ -102,7 +105,8 @@ hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st);
 size_t decode_smem_bytes(int d, int G);
 size_t score_lines_smem(int w, int dtype, int d, int mode);
 hipError_t run_select(const SelectArgs& a, hipStream_t st);
-hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st);
+hipError_t run_topb(const TopbArgs& a, int BK, uint32_t* scratch, hipStream_t st);   // scratch: topb_scratch_words(BK, len) words
+size_t topb_scratch_words(int BK, int64_t len);
 hipError_t run_gather_rows(const void* src, void* dst, const int32_t* keep_idx, const int32_t* keep_cnt,
                            int BK, int64_t len, int budget, int row_bytes, hipStream_t st);
 hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st);

@@ -15,8 +15,9 @@
 //                 stages the sorted lists and their overlap prefix sums in LDS ahead of the walk.
 //   emit_kernel   one workgroup per (head, list): the chosen prefix of a sorted list becomes an
 //                 ascending index list (bitmap in LDS + prefix popcount).
-//   topb_kernel   Alg. 3: the `budget` largest scores per KV head by 4-pass radix select on the
-//                 float bit patterns, ties broken towards smaller indices, ascending output.
+//   topb_*        Alg. 3: the `budget` largest scores per KV head by a three-digit radix select on the
+//                 float bit patterns, ties broken towards smaller indices, ascending output; a head's
+//                 scores are spread over many workgroups, one launch per step.
 #include "ls_device.h"
 #include "ls_internal.h"
 
@@ -511,141 +512,188 @@ __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
 }
 
 // ---- top-B retention ------------------------------------------------------------------------------
-// grid (B*Hkv).  keep_idx [BK][budget] ascending; keep_cnt = min(budget, len).
-// Radix select on the descending keys (four 8-bit digits, most significant first) finds the key K* of
-// the budget-th largest score; then one counting sweep and one writing sweep over 64-element segments
-// emit, in index order, every element above K* and the first few equal to it.
-constexpr int TOPB_THREADS = 1024;
-constexpr int TOPB_WAVES = TOPB_THREADS / 64;
-constexpr int TOPB_BATCH = 16;                          // independent loads in flight per lane
-constexpr int TOPB_MAX_SEG = (int)(TOPB_MAX_LEN / 64);
+// keep_idx [BK][budget] ascending; keep_cnt = min(budget, len).
+// Radix select on the descending keys in three digits (11 + 11 + 10 bits, most significant first) finds the
+// key K* of the budget-th largest score; then every element above K* and the first few equal to it are
+// written in index order.  One KV head has too few elements to need a chip but too many for one CU to be
+// quick, so a head's scores are cut into chunks of TB_CHUNK, one workgroup each, and the steps are separate
+// launches that meet in small global arrays: hist [BK][3][TB_BINS] (zeroed by the first launch), state
+// [BK][3][2] (prefix and elements still wanted after each digit) and cnt [BK][chunks][2].
+constexpr int TB_THREADS = 1024;
+constexpr int TB_CHUNK = 2048;
+constexpr int TB_BINS = 2048;
 
-__global__ __launch_bounds__(TOPB_THREADS) void topb_kernel(TopbArgs a) {
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t sel_prefix, sel_remaining;
-    __shared__ uint32_t wsum_gt[TOPB_WAVES], wsum_eq[TOPB_WAVES];
-    __shared__ uint32_t seg_gt[TOPB_MAX_SEG], seg_eq[TOPB_MAX_SEG];
-    const int bk = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+__device__ __forceinline__ uint32_t tb_digit(uint32_t key, int pass) {
+    return pass == 0 ? key >> 21 : pass == 1 ? (key >> 10) & 2047u : key & 1023u;
+}
+__device__ __forceinline__ uint32_t tb_himask(int pass) { return pass == 0 ? 0u : pass == 1 ? 0xFFE00000u : 0xFFFFFC00u; }
+__device__ __forceinline__ int tb_shift(int pass) { return pass == 0 ? 21 : pass == 1 ? 10 : 0; }
+
+// All threads of a workgroup: from the histogram of digit `pass` (among the keys that match `prefix`) and the
+// number of elements still wanted, the digit that holds the wanted-th element; returns the longer prefix and
+// what is still wanted inside it.
+__device__ __forceinline__ void tb_pick(const uint32_t* hist, int pass, uint32_t prefix, uint32_t rem,
+                                        uint32_t* wsum, uint32_t* res, uint32_t& prefix_out, uint32_t& rem_out) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+    const uint32_t v = h0 + h1;
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
+    __syncthreads();                                       // wsum / res may still be read from an earlier call
+    if (lane == 63) wsum[wv] = inc;
+    __syncthreads();
+    uint32_t ex = inc - v;
+    for (int w = 0; w < wv; ++w) ex += wsum[w];
+    if (ex < rem && rem <= ex + v) {                       // exactly one thread: the total is at least rem
+        const uint32_t r = rem - ex;
+        const uint32_t d = 2u * tid + (r > h0 ? 1u : 0u);
+        res[0] = prefix | (d << tb_shift(pass));
+        res[1] = r > h0 ? r - h0 : r;
+    }
+    __syncthreads();
+    prefix_out = res[0]; rem_out = res[1];
+}
+
+__global__ void topb_zero_kernel(uint32_t* p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0u;
+}
+
+// grid (chunks, BK): histogram of digit PASS over this chunk's keys that match the prefix found so far
+template <int PASS>
+__global__ __launch_bounds__(TB_THREADS) void topb_hist_kernel(TopbArgs a) {
+    __shared__ uint32_t lh[TB_BINS];
+    __shared__ uint32_t wsum[16], res[2];
+    const int chunk = blockIdx.x, bk = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int64_t len = a.len;
-    const float* sc = a.score + (int64_t)bk * len;
-    int32_t* out = a.keep_idx + (int64_t)bk * a.budget;
     const int64_t keep = a.budget < len ? a.budget : len;
-    if (tid == 0) a.keep_cnt[bk] = (int32_t)keep;
+    if (keep == len) return;                               // everything is kept: the write step needs no threshold
+    uint32_t* hist = a.hist + (int64_t)bk * 3 * TB_BINS;
+    uint32_t* state = a.state + (int64_t)bk * 6;
+    uint32_t prefix = 0u, rem = (uint32_t)keep;
+    if (PASS >= 1) {
+        if (PASS == 2) { prefix = state[0]; rem = state[1]; }
+        tb_pick(hist + (PASS - 1) * TB_BINS, PASS - 1, prefix, rem, wsum, res, prefix, rem);
+        if (chunk == 0 && tid == 0) { state[2 * (PASS - 1)] = prefix; state[2 * (PASS - 1) + 1] = rem; }
+    }
+    for (int i = tid; i < TB_BINS; i += TB_THREADS) lh[i] = 0u;
+    __syncthreads();
+    const float* sc = a.score + (int64_t)bk * len;
+    uint32_t kb[TB_CHUNK / TB_THREADS];
+#pragma unroll
+    for (int q = 0; q < TB_CHUNK / TB_THREADS; ++q) {
+        const int64_t i = (int64_t)chunk * TB_CHUNK + q * TB_THREADS + tid;
+        kb[q] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (int q = 0; q < TB_CHUNK / TB_THREADS; ++q) {
+        // scores of one head crowd into few digits: lanes with the same digit add once, through their first lane
+        const int64_t i = (int64_t)chunk * TB_CHUNK + q * TB_THREADS + tid;
+        const bool on = i < len && (kb[q] & tb_himask(PASS)) == prefix;
+        const uint32_t digit = tb_digit(kb[q], PASS);
+        uint64_t peers = __ballot(on);
+#pragma unroll
+        for (int b = 0; b < 11; ++b) {
+            const bool bit = (digit >> b) & 1u;
+            const uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        if (on && __ffsll((unsigned long long)peers) - 1 == lane) atomicAdd(&lh[digit], (uint32_t)__popcll(peers));
+    }
+    __syncthreads();
+    for (int i = tid; i < TB_BINS; i += TB_THREADS) if (lh[i]) atomicAdd(&hist[PASS * TB_BINS + i], lh[i]);
+}
+
+// grid (chunks, BK): K* and the number of elements equal to it that are kept; per chunk, how many of its
+// elements lie above K* and how many equal it
+__global__ __launch_bounds__(TB_THREADS) void topb_count_kernel(TopbArgs a) {
+    __shared__ uint32_t wsum[16], res[2], wg[16], we[16];
+    const int chunk = blockIdx.x, bk = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int64_t len = a.len;
+    const int64_t keep = a.budget < len ? a.budget : len;
+    if (keep == len) return;
+    uint32_t* state = a.state + (int64_t)bk * 6;
+    uint32_t kstar, need_eq;
+    tb_pick(a.hist + ((int64_t)bk * 3 + 2) * TB_BINS, 2, state[2], state[3], wsum, res, kstar, need_eq);
+    if (chunk == 0 && tid == 0) { state[4] = kstar; state[5] = need_eq; }
+    const float* sc = a.score + (int64_t)bk * len;
+    uint32_t g = 0, e = 0;
+#pragma unroll
+    for (int q = 0; q < TB_CHUNK / TB_THREADS; ++q) {
+        const int64_t i = (int64_t)chunk * TB_CHUNK + q * TB_THREADS + tid;
+        const uint32_t key = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
+        g += (uint32_t)__popcll(__ballot(i < len && key < kstar));
+        e += (uint32_t)__popcll(__ballot(i < len && key == kstar));
+    }
+    if (lane == 0) { wg[wv] = g; we[wv] = e; }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t tg = 0, te = 0;
+        for (int w = 0; w < 16; ++w) { tg += wg[w]; te += we[w]; }
+        a.cnt[((int64_t)bk * a.chunks + chunk) * 2] = tg;
+        a.cnt[((int64_t)bk * a.chunks + chunk) * 2 + 1] = te;
+    }
+}
+
+// grid (chunks, BK): slot of a kept element = kept elements before it; kept = above K*, or equal to it among
+// the first need_eq of those
+__global__ __launch_bounds__(TB_THREADS) void topb_write_kernel(TopbArgs a) {
+    __shared__ uint32_t seg_g[TB_CHUNK / 64], seg_e[TB_CHUNK / 64], base_s[2];
+    const int chunk = blockIdx.x, bk = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int64_t len = a.len;
+    const int64_t keep = a.budget < len ? a.budget : len;
+    int32_t* out = a.keep_idx + (int64_t)bk * a.budget;
+    if (chunk == 0 && tid == 0) a.keep_cnt[bk] = (int32_t)keep;
     if (keep == len) {
-        for (int64_t i = tid; i < len; i += TOPB_THREADS) out[i] = (int32_t)i;
+#pragma unroll
+        for (int q = 0; q < TB_CHUNK / TB_THREADS; ++q) {
+            const int64_t i = (int64_t)chunk * TB_CHUNK + q * TB_THREADS + tid;
+            if (i < len) out[i] = (int32_t)i;
+        }
         return;
     }
-    if (tid == 0) { sel_prefix = 0u; sel_remaining = (uint32_t)keep; }
-    __syncthreads();
-    for (int pass = 3; pass >= 0; --pass) {
-        const int shift = 8 * pass;
-        if (tid < 256) hist[tid] = 0u;
-        __syncthreads();
-        const uint32_t prefix = sel_prefix;
-        const uint32_t himask = pass == 3 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int64_t i0 = tid; i0 < len; i0 += TOPB_BATCH * TOPB_THREADS) {
-            uint32_t kb[TOPB_BATCH];
+    const uint32_t* state = a.state + (int64_t)bk * 6;
+    const uint32_t kstar = state[4], need_eq = state[5];
+    const float* sc = a.score + (int64_t)bk * len;
+    // elements above / equal to K* in the chunks before this one (one wave adds them up, lanes striding)
+    if (wv == 0) {
+        uint32_t g = 0, e = 0;
+        for (int c = lane; c < chunk; c += 64) { g += a.cnt[((int64_t)bk * a.chunks + c) * 2]; e += a.cnt[((int64_t)bk * a.chunks + c) * 2 + 1]; }
 #pragma unroll
-            for (int j = 0; j < TOPB_BATCH; ++j) {
-                const int64_t i = i0 + j * TOPB_THREADS;
-                kb[j] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
-            }
-#pragma unroll
-            for (int j = 0; j < TOPB_BATCH; ++j) {
-                // scores of one head crowd into few digits: lanes with the same digit add once, through their first lane
-                const bool on = i0 + j * TOPB_THREADS < len && (kb[j] & himask) == prefix;
-                const uint32_t digit = (kb[j] >> shift) & 255u;
-                uint64_t peers = __ballot(on);
-#pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                    const bool bit = (digit >> b) & 1u;
-                    const uint64_t m = __ballot(bit);
-                    peers &= bit ? m : ~m;
-                }
-                if (on && __ffsll((unsigned long long)peers) - 1 == lane) atomicAdd(&hist[digit], (uint32_t)__popcll(peers));
-            }
-        }
-        __syncthreads();
-        if (wv == 0) {
-            // digit whose running count first reaches what is still needed: four digits per lane, scanned over the wave
-            const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-            const uint32_t s = h0 + h1 + h2 + h3;
-            uint32_t inc = s;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
-            const uint32_t rem = sel_remaining;
-            const uint64_t reach = __ballot(inc >= rem);   // never empty: the prefix holds at least rem elements
-            if (__ffsll((unsigned long long)reach) - 1 == lane) {
-                uint32_t r = rem - (inc - s), d = 4u * lane;
-                if (h0 < r) { r -= h0; ++d; if (h1 < r) { r -= h1; ++d; if (h2 < r) { r -= h2; ++d; } } }
-                sel_prefix = prefix | (d << shift);
-                sel_remaining = r;                     // elements equal to the prefix so far that are still needed
-            }
-        }
-        __syncthreads();
+        for (int off = 32; off > 0; off >>= 1) { g += __shfl_xor(g, off, 64); e += __shfl_xor(e, off, 64); }
+        if (lane == 0) { base_s[0] = g; base_s[1] = e; }
     }
-    const uint32_t kstar = sel_prefix;                 // smaller key = larger score
-    const uint32_t need_eq = sel_remaining;            // elements with key == kstar to keep (smallest indices)
-    const int64_t nseg = (len + 63) >> 6;
-    // counting sweep: per 64-element segment, how many lie above K* and how many equal it
-    for (int64_t s0 = wv; s0 < nseg; s0 += TOPB_BATCH * TOPB_WAVES) {
-        uint32_t kb[TOPB_BATCH];
+    uint32_t kb[TB_CHUNK / TB_THREADS];
 #pragma unroll
-        for (int j = 0; j < TOPB_BATCH; ++j) {
-            const int64_t i = (s0 + j * TOPB_WAVES) * 64 + lane;
-            kb[j] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
-        }
-#pragma unroll
-        for (int j = 0; j < TOPB_BATCH; ++j) {
-            const int64_t s = s0 + j * TOPB_WAVES, i = s * 64 + lane;
-            const uint64_t gt = __ballot(i < len && kb[j] < kstar), eq = __ballot(i < len && kb[j] == kstar);
-            if (s < nseg && lane == 0) { seg_gt[s] = (uint32_t)__popcll(gt); seg_eq[s] = (uint32_t)__popcll(eq); }
-        }
+    for (int q = 0; q < TB_CHUNK / TB_THREADS; ++q) {
+        const int64_t i = (int64_t)chunk * TB_CHUNK + q * TB_THREADS + tid;
+        kb[q] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
+        const uint64_t gm = __ballot(i < len && kb[q] < kstar), em = __ballot(i < len && kb[q] == kstar);
+        if (lane == 0) { seg_g[q * 16 + wv] = (uint32_t)__popcll(gm); seg_e[q * 16 + wv] = (uint32_t)__popcll(em); }
     }
     __syncthreads();
-    {   // exclusive scan of the segment counts, in place: a run of consecutive segments per thread
-        const int per = (int)((nseg + TOPB_THREADS - 1) / TOPB_THREADS);
-        const int64_t b = (int64_t)tid * per, e = b + per < nseg ? b + per : nseg;
-        uint32_t tg = 0, te = 0;
-        for (int64_t s = b; s < e; ++s) { tg += seg_gt[s]; te += seg_eq[s]; }
-        uint32_t ig = tg, ie = te;
+    if (wv == 0) {                                         // exclusive scan over the chunk's 64-element segments
+        uint32_t g = lane < TB_CHUNK / 64 ? seg_g[lane] : 0u, e = lane < TB_CHUNK / 64 ? seg_e[lane] : 0u;
+        uint32_t ig = g, ie = e;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const uint32_t ug = __shfl_up(ig, off, 64), ue = __shfl_up(ie, off, 64);
             if (lane >= off) { ig += ug; ie += ue; }
         }
-        if (lane == 63) { wsum_gt[wv] = ig; wsum_eq[wv] = ie; }
-        __syncthreads();
-        uint32_t pg = ig - tg, pe = ie - te;
-        for (int w = 0; w < wv; ++w) { pg += wsum_gt[w]; pe += wsum_eq[w]; }
-        for (int64_t s = b; s < e; ++s) {
-            const uint32_t g = seg_gt[s], q = seg_eq[s];
-            seg_gt[s] = pg; seg_eq[s] = pe;
-            pg += g; pe += q;
-        }
+        if (lane < TB_CHUNK / 64) { seg_g[lane] = base_s[0] + ig - g; seg_e[lane] = base_s[1] + ie - e; }
     }
     __syncthreads();
-    // writing sweep: slot = kept elements before me; kept = above K*, or equal to it among the first need_eq
     const uint64_t below = (1ull << lane) - 1ull;
-    for (int64_t s0 = wv; s0 < nseg; s0 += TOPB_BATCH * TOPB_WAVES) {
-        uint32_t kb[TOPB_BATCH];
 #pragma unroll
-        for (int j = 0; j < TOPB_BATCH; ++j) {
-            const int64_t i = (s0 + j * TOPB_WAVES) * 64 + lane;
-            kb[j] = i < len ? desc_key(sc[i]) : 0xFFFFFFFFu;
-        }
-#pragma unroll
-        for (int j = 0; j < TOPB_BATCH; ++j) {
-            const int64_t s = s0 + j * TOPB_WAVES, i = s * 64 + lane;
-            const bool gt = i < len && kb[j] < kstar, eq = i < len && kb[j] == kstar;
-            const uint64_t gtm = __ballot(gt), eqm = __ballot(eq);
-            if (s < nseg) {
-                const uint32_t gt_before = seg_gt[s] + (uint32_t)__popcll(gtm & below);
-                const uint32_t eq_before = seg_eq[s] + (uint32_t)__popcll(eqm & below);
-                const uint32_t eq_kept_before = eq_before < need_eq ? eq_before : need_eq;
-                if (gt || (eq && eq_before < need_eq)) out[gt_before + eq_kept_before] = (int32_t)i;
-            }
-        }
+    for (int q = 0; q < TB_CHUNK / TB_THREADS; ++q) {
+        const int64_t i = (int64_t)chunk * TB_CHUNK + q * TB_THREADS + tid;
+        const bool gt = i < len && kb[q] < kstar, eq = i < len && kb[q] == kstar;
+        const uint64_t gm = __ballot(gt), em = __ballot(eq);
+        const uint32_t gt_before = seg_g[q * 16 + wv] + (uint32_t)__popcll(gm & below);
+        const uint32_t eq_before = seg_e[q * 16 + wv] + (uint32_t)__popcll(em & below);
+        const uint32_t eq_kept_before = eq_before < need_eq ? eq_before : need_eq;
+        if (gt || (eq && eq_before < need_eq)) out[gt_before + eq_kept_before] = (int32_t)i;
     }
 }
 
@@ -680,9 +728,24 @@ hipError_t run_select(const SelectArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t run_topb(const TopbArgs& a, int BK, hipStream_t st) {
-    if (a.len < 1 || a.len > TOPB_MAX_LEN || a.budget < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(topb_kernel, dim3(BK), dim3(TOPB_THREADS), 0, st, a);
+int topb_chunks(int64_t len) { return (int)((len + TB_CHUNK - 1) / TB_CHUNK); }
+size_t topb_scratch_words(int BK, int64_t len) { return (size_t)BK * (3 * TB_BINS + 6 + 2 * (size_t)topb_chunks(len)); }
+
+hipError_t run_topb(const TopbArgs& a0, int BK, uint32_t* scratch, hipStream_t st) {
+    if (a0.len < 1 || a0.len > TOPB_MAX_LEN || a0.budget < 1) return hipErrorInvalidValue;
+    TopbArgs a = a0;
+    a.chunks = topb_chunks(a.len);
+    a.hist = scratch;
+    a.state = a.hist + (size_t)BK * 3 * TB_BINS;
+    a.cnt = a.state + (size_t)BK * 6;
+    const dim3 grid(a.chunks, BK);
+    const int nz = BK * 3 * TB_BINS;
+    hipLaunchKernelGGL(topb_zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, st, a.hist, nz);
+    hipLaunchKernelGGL(topb_hist_kernel<0>, grid, dim3(TB_THREADS), 0, st, a);
+    hipLaunchKernelGGL(topb_hist_kernel<1>, grid, dim3(TB_THREADS), 0, st, a);
+    hipLaunchKernelGGL(topb_hist_kernel<2>, grid, dim3(TB_THREADS), 0, st, a);
+    hipLaunchKernelGGL(topb_count_kernel, grid, dim3(TB_THREADS), 0, st, a);
+    hipLaunchKernelGGL(topb_write_kernel, grid, dim3(TB_THREADS), 0, st, a);
     return hipGetLastError();
 }
 

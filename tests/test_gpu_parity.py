@@ -210,6 +210,7 @@ def test_prefill_matches_oracle(oracle, pattern, B, Hq, Hkv, n, n_hat, d, dtype)
     (2, 8, 2, 900, 16, 128, 128, "bf16"),
     (1, 4, 1, 300, 16, 64, 64, "f32"),
     (1, 4, 4, 100, 8, 64, 256, "bf16"),    # budget >= len keeps everything
+    (1, 4, 2, 5000, 16, 64, 700, "bf16"),  # several selection chunks, the last one ragged
 ])
 def test_compress_matches_oracle(oracle, B, Hq, Hkv, ln, n_obs, d, budget, dtype):
     q, k, v = inputs.make_plain(B, Hq, Hkv, ln, n_obs, d, dtype=dtype, seed=ln, q_scale=2.0)
@@ -240,6 +241,24 @@ def test_compress_matches_oracle(oracle, B, Hq, Hkv, ln, n_obs, d, budget, dtype
                 assert np.all(np.abs(ref["score"][b, j][diff] - thr) <= 1e-3 * thr)
             np.testing.assert_array_equal(k_out[b, j, :cnt].float().cpu().numpy(), k[b, j][got])
             np.testing.assert_array_equal(v_out[b, j, :cnt].float().cpu().numpy(), v[b, j][got])
+
+
+def test_compress_ties_across_chunks(oracle):
+    """Repeated key rows give exactly equal scores all over the cache: the threshold falls among ties that span
+    several selection chunks and must be resolved towards the smaller indices."""
+    B, Hq, Hkv, ln, n_obs, d, budget = 1, 2, 1, 4500, 8, 64, 1000
+    q, k, v = inputs.make_plain(B, Hq, Hkv, ln, n_obs, d, dtype="bf16", seed=5, q_scale=2.0)
+    k = k[:, :, np.arange(ln) % 37].copy()
+    pipe = Pipeline(q, k, v, n_obs, "bf16", budget=budget)
+    keep_idx = torch.full((B, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    keep_cnt = torch.zeros((B, Hkv), dtype=torch.int32, device="cuda")
+    pipe.ctx.ls_kv_compress(pipe.shape, budget, pipe.q, pipe.k, None, keep_idx, keep_cnt)
+    score = torch.empty((B, Hkv, ln), dtype=torch.float32, device="cuda")
+    pipe.ctx.debug_compress_score(pipe.shape, score)
+    score = score.cpu().numpy()
+    assert len(np.unique(score[0, 0, : ln - n_obs])) <= 37       # the ties are really there
+    assert int(keep_cnt.cpu().numpy()[0, 0]) == budget
+    np.testing.assert_array_equal(keep_idx.cpu().numpy()[0, 0], oracle.topb(score[0, 0], budget))
 
 
 # --------------------------------------------------------------------------- argument errors
