@@ -81,7 +81,22 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) { const int i = i0 + j * 1024; o8[j] = i < ns ? si[i] : -1; }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) if (o8[j] >= 0 && o8[j] < n) atomicOr(&sm[o8[j] >> 5], 1u << (o8[j] & 31));
+        for (int j = 0; j < 8; ++j) {
+            // The list is ascending, so neighbouring lanes mostly hit the same bitmap word: their bits are OR-ed
+            // across each run of equal words first (five doubling steps reach 32 lanes) and the run's first lane,
+            // and every 32nd lane, does the one atomic.  Correct for any order of the list.
+            const bool ok = o8[j] >= 0 && o8[j] < n;
+            const int wd = ok ? o8[j] >> 5 : -1 - (tid & 63);
+            uint32_t m = ok ? 1u << (o8[j] & 31) : 0u;
+#pragma unroll
+            for (int off = 1; off < 32; off <<= 1) {
+                const uint32_t tm = __shfl_down(m, off, 64);
+                const int tw = __shfl_down(wd, off, 64);
+                if ((tid & 63) + off < 64 && tw == wd) m |= tm;
+            }
+            const int pw = __shfl_up(wd, 1, 64);
+            if (ok && (((tid & 31) == 0) || pw != wd)) atomicOr(&sm[wd], m);
+        }
     }
     __syncthreads();
     int mine = 0;

@@ -475,6 +475,10 @@ __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
     const int cnt = list == 0 ? a.s_cnt[bh] : a.v_cnt[bh];
     int32_t* out = list == 0 ? a.s_idx + (int64_t)bh * a.cap_s : a.v_idx + (int64_t)bh * a.cap_v;
     const int cap = list == 0 ? a.cap_s : a.cap_v;
+    if (cnt >= n) {                                        // every line was taken: the list is 0 .. n-1
+        for (int64_t i = tid; i < n && i < cap; i += 1024) out[i] = (int32_t)i;
+        return;
+    }
     for (int i = tid; i < words; i += 1024) bm[i] = 0u;
     if (tid == 0) carry = 0u;
     __syncthreads();
