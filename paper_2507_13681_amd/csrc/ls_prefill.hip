@@ -76,7 +76,20 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     for (int i = tid; i < words; i += blockDim.x) sm[i] = 0u;
     if (tid == 0) total_bits = 0;
     __syncthreads();
-    for (int i0 = tid; i0 < ns; i0 += 8 * 1024) {          // eight independent loads in flight per thread
+    // every diagonal selected (a head the walk gave up sparsifying): the list is 0 .. n-1, checked while it is read
+    bool ident = ns == (int)n;
+    if (ident) {
+        for (int i0 = tid; i0 < ns; i0 += 8 * 1024) {
+            int32_t o8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { const int i = i0 + j * 1024; o8[j] = i < ns ? si[i] : i; }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ident = ident && o8[j] == i0 + j * 1024;
+        }
+        ident = __syncthreads_and(ident);
+        if (ident) for (int i = tid; i < (int)((n + 31) / 32); i += blockDim.x) sm[i] = (i == (int)(n / 32)) ? ((1u << (n & 31)) - 1u) : 0xFFFFFFFFu;
+    }
+    for (int i0 = tid; i0 < (ident ? 0 : ns); i0 += 8 * 1024) {          // eight independent loads in flight per thread
         int32_t o8[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) { const int i = i0 + j * 1024; o8[j] = i < ns ? si[i] : -1; }
