@@ -346,19 +346,23 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     wait_ready(0, 0);
     wait_ready(1, 0);
 
-    // What the lanes need of a list when its head is at `h`: entry h + lane (weight, overlap prefix, length)
-    // and the head's own three values.  Re-read only when the head of that list moves; the read for the
-    // head position after the current run is issued before the run's sums are settled, so its LDS latency
-    // hides behind them.
-    struct View { float cw, pre, cl, w0, l0, ol0; bool ok, has; };
+    // What the lanes need of a list when its head is at `h`: lane l looks at the entries h + 2l and h + 2l + 1
+    // (weight, overlap prefix, length), every lane at the head's own three values.  Re-read only when the head of
+    // that list moves; the read for the head position after the current run is issued before the run's sums are
+    // settled, so its LDS latency hides behind them.  (A window holds WALK_WIN entries from a start that is at
+    // most WALK_STRIDE - 1 before the head: the 128 entries after the head are always inside it.)
+    struct View { float cw[2], pre[2], cl[2], w0, l0, ol0; bool ok[2], has; };
     auto view = [&](int l, int h) {
         const WalkWin& W = win[l][curw[l] & 1];
         const int base = curw[l] * WALK_STRIDE;
         View r;
-        const int i = h + lane;
-        r.ok = i < n && (i - base) < WALK_WIN;
-        const int ii = r.ok ? i - base : 0;
-        r.cw = W.cw[ii]; r.pre = W.pre[ii]; r.cl = W.cl[ii];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = h + 2 * lane + e;
+            r.ok[e] = i < n && (i - base) < WALK_WIN;
+            const int ii = r.ok[e] ? i - base : 0;
+            r.cw[e] = W.cw[ii]; r.pre[e] = W.pre[ii]; r.cl[e] = W.cl[ii];
+        }
         r.has = h < n;
         const int hh = r.has ? h - base : 0;
         r.w0 = r.has ? W.cw[hh] : 0.f;                     // an exhausted list: no weight, and its overlap sum
@@ -367,6 +371,13 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         return r;
     };
     View S = view(0, 0), V = view(1, 0);
+    // position of the first set bit in the order entry 0 of lane 0, entry 1 of lane 0, entry 0 of lane 1, ...
+    // (128 if neither mask has one)
+    auto first_of = [](uint64_t m0, uint64_t m1) -> int {
+        const int f0 = m0 ? 2 * (__ffsll((unsigned long long)m0) - 1) : 128;
+        const int f1 = m1 ? 2 * (__ffsll((unsigned long long)m1) - 1) + 1 : 128;
+        return f0 < f1 ? f0 : f1;
+    };
 
     while (!failed) {
         const int is = head[0], iv = head[1];
@@ -389,64 +400,75 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             V = view(1, iv);
         }
         const bool s_has = S.has, v_has = V.has;
-        // lane j: decision if the walk has taken j more slashes (iv frozen)
-        int i = is + lane;
-        float ds = __fsub_rn(S.cw, V.ol0);
-        float dv = __fsub_rn(V.w0, S.pre);
-        float cs = __fsub_rn(S.cl, (float)iv); if (cs < 1.0f) cs = 1.0f;
-        float cv = __fsub_rn(V.l0, (float)i); if (cv < 1.0f) cv = 1.0f;
-        bool take = !v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
-        bool dead = !(ds > 0.f) && (!v_has || !(dv > 0.f));
-        uint64_t bal = __ballot(S.ok && take);
-        int run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
-        float gain = ds;
+        // entry e of lane j: the decision if the walk has taken 2j + e more slashes (iv frozen)
+        float gain[2];
+        bool take[2], dead[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = is + 2 * lane + e;
+            const float ds = __fsub_rn(S.cw[e], V.ol0);
+            const float dv = __fsub_rn(V.w0, S.pre[e]);
+            float cs = __fsub_rn(S.cl[e], (float)iv); if (cs < 1.0f) cs = 1.0f;
+            float cv = __fsub_rn(V.l0, (float)i); if (cv < 1.0f) cv = 1.0f;
+            take[e] = S.ok[e] && (!v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));
+            dead[e] = !(ds > 0.f) && (!v_has || !(dv > 0.f));
+            gain[e] = ds;
+        }
+        int run = first_of(~__ballot(take[0]), ~__ballot(take[1]));
         int which = 0;
         if (run == 0) {
-            // the head pick is a vertical; lane j: decision if j more verticals are taken (is frozen)
+            // the head pick is a vertical; entry e of lane j: the decision if 2j + e more verticals are taken (is frozen)
             which = 1;
-            i = iv + lane;
-            dv = __fsub_rn(V.cw, S.ol0);
-            ds = __fsub_rn(S.w0, V.pre);
-            cv = __fsub_rn(V.cl, (float)is); if (cv < 1.0f) cv = 1.0f;
-            cs = __fsub_rn(S.l0, (float)i); if (cs < 1.0f) cs = 1.0f;
-            take = !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
-            dead = !(dv > 0.f) && (!s_has || !(ds > 0.f));
-            bal = __ballot(V.ok && take);
-            run = __ffsll((unsigned long long)~bal) - 1; if (run < 0) run = 64;
-            gain = dv;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int i = iv + 2 * lane + e;
+                const float dv = __fsub_rn(V.cw[e], S.ol0);
+                const float ds = __fsub_rn(S.w0, V.pre[e]);
+                float cv = __fsub_rn(V.cl[e], (float)is); if (cv < 1.0f) cv = 1.0f;
+                float cs = __fsub_rn(S.l0, (float)i); if (cs < 1.0f) cs = 1.0f;
+                take[e] = V.ok[e] && !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
+                dead[e] = !(dv > 0.f) && (!s_has || !(ds > 0.f));
+                gain[e] = dv;
+            }
+            run = first_of(~__ballot(take[0]), ~__ballot(take[1]));
         }
-        if (run == 0) break;                   // cannot happen (lane 0 repeats the head's test); never spin
+        if (run == 0) break;                   // cannot happen (entry 0 of lane 0 repeats the head's test); never spin
         // picks 0 .. run-1 come from list `which`; stop early when no head has a positive gain
-        const uint64_t deadb = __ballot(dead);
-        int stop_dead = 64;
-        if (early && deadb) stop_dead = __ffsll((unsigned long long)deadb) - 1;
+        int stop_dead = 128;
+        if (early) stop_dead = first_of(__ballot(dead[0]), __ballot(dead[1]));
         // picks 0 .. limit-1 are applied; the running sum is accumulated pick by pick
         const int limit = run < stop_dead ? run : stop_dead;
         // the list's view after the run (used only if the whole run is applied and the walk goes on; a
         // window change re-reads it)
         const View nxt = view(which, head[which] + limit);
-        // Lane j ends up with the running sum after pick j: x_j = x_{j-1} + gain_j, lane 0 starting from
-        // `sum`.  One pass of "take the left neighbour's value and add my gain" over all lanes settles one
-        // more lane, in order, so `limit` passes reproduce the pick-by-pick additions exactly; the first
-        // lane whose sum reaches the target is the pick the loop of the definition stops after.
-        // (Lane 0 has no left neighbour: the shift hands it 0 and its addend is sum + gain_0, so it
-        // holds exactly that.)
-        const float addend = lane == 0 ? __fadd_rn(sum, gain) : gain;
-        float x = 0.f;
+        // Lane j ends up with the running sums after its two picks: x0_j = x1_{j-1} + gain0_j, x1_j = x0_j + gain1_j,
+        // lane 0 starting from `sum`.  One pass of "take the left neighbour's x1, add my two gains one after the
+        // other" over all lanes settles one more lane, in order, so ceil(limit / 2) passes reproduce the
+        // pick-by-pick additions exactly; the first entry whose sum reaches the target is the pick the loop of
+        // the definition stops after.  (Lane 0 has no left neighbour: the shift hands it 0 and its first addend
+        // is sum + gain0, so it holds exactly that.)
+        const float addend0 = lane == 0 ? __fadd_rn(sum, gain[0]) : gain[0];
+        float x0 = 0.f, x1 = 0.f;
         for (int p0 = 0; p0 < limit; p0 += 8) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
-                    0, __builtin_bit_cast(int, x), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
-                x = __fadd_rn(left, addend);
+                    0, __builtin_bit_cast(int, x1), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+                x0 = __fadd_rn(left, addend0);
+                x1 = __fadd_rn(x0, gain[1]);
             }
         }
-        const uint64_t lanes = limit >= 64 ? ~0ull : ((1ull << limit) - 1ull);
-        const uint64_t hit = __ballot(!(x < target)) & lanes;
-        int taken = limit;
-        const bool reached = hit != 0ull;
-        if (reached) taken = __ffsll((unsigned long long)hit);          // 1-based position = picks applied
-        if (taken > 0) sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), taken - 1));
+        // entries below `limit`: entry 0 of lane j is pick 2j, entry 1 is pick 2j + 1
+        const int n0 = (limit + 1) >> 1, n1 = limit >> 1;
+        const uint64_t lanes0 = n0 >= 64 ? ~0ull : ((1ull << n0) - 1ull);
+        const uint64_t lanes1 = n1 >= 64 ? ~0ull : ((1ull << n1) - 1ull);
+        const int hit = first_of(__ballot(!(x0 < target)) & lanes0, __ballot(!(x1 < target)) & lanes1);
+        const bool reached = hit < 128;
+        const int taken = reached ? hit + 1 : limit;                    // picks applied
+        if (taken > 0) {
+            const float xs = ((taken - 1) & 1) ? x1 : x0;
+            sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xs), (taken - 1) >> 1));
+        }
         const bool exhausted = !reached && stop_dead < run;      // the pick after the last one has no positive gain
         head[which] += taken;
         if (exhausted) { head[0] = n; head[1] = n; break; }
