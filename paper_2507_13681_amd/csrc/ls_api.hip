@@ -73,9 +73,15 @@ inline float scale_log2e(const ls_shape* s) {
     return sc * 1.44269504088896340736f;
 }
 
+// per key block max / sum of every scored row; later the 8 partial totals of every head
+inline size_t part_floats(const ls_shape* s) {
+    const size_t BH = (size_t)s->B * s->Hq;
+    const size_t a = BH * s->w * nkb_of(s->n) * 2, b = BH * 8;
+    return a > b ? a : b;
+}
 size_t ws_score(const ls_shape* s, bool lines) {
     const size_t BH = (size_t)s->B * s->Hq;
-    size_t b = up(BH * s->w * nkb_of(s->n) * 2 * 4) + up(BH * s->w * 2 * 4);
+    size_t b = up(part_floats(s) * 4) + up(BH * s->w * 2 * 4);
     if (lines) b += up(2 * BH * (size_t)s->n * 2 * 4);
     return b;
 }
@@ -152,7 +158,7 @@ int ls_score(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_p
     a.q = q_win; a.k = k; a.q_pos = q_pos; a.n = s->n; a.w = s->w; a.G = s->Hq / s->Hkv; a.Hq = s->Hq;
     a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
     Bump bp{c->ws, c->ws_bytes, 0};
-    a.part = bp.take<float>((size_t)a.BH * a.w * a.nkb * 2);
+    a.part = bp.take<float>(part_floats(s));
     a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
     a.spart = bp.take<float>(2 * (size_t)a.BH * (size_t)a.n * 2);
     if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_score: workspace of %zu bytes is too small", c->ws_bytes);
@@ -271,7 +277,7 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
     a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
     const int BK = s->B * s->Hkv;
     Bump bp{c->ws, c->ws_bytes, 0};
-    a.part = bp.take<float>((size_t)a.BH * a.w * a.nkb * 2);
+    a.part = bp.take<float>(part_floats(s));
     a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
     a.gscore = bp.take<float>((size_t)BK * (size_t)a.n);
     uint32_t* tb_scratch = bp.take<uint32_t>(ls::topb_scratch_words(BK, s->n));
@@ -375,7 +381,7 @@ int ls_profile_prefill_kernel_ms(ls_ctx* c, double* mean_ms, int32_t* launches) 
 int ls_debug_copy_compress_score(ls_ctx* c, const ls_shape* s, float* dst_device, void* stream) {
     if (!c || !s || !dst_device) return LS_EINVAL;
     const size_t BH = (size_t)s->B * s->Hq;
-    const size_t off = up(BH * s->w * nkb_of(s->n) * 2 * 4) + up(BH * s->w * 2 * 4);
+    const size_t off = up(part_floats(s) * 4) + up(BH * s->w * 2 * 4);
     const size_t bytes = (size_t)s->B * s->Hkv * (size_t)s->n * 4;
     if (off + bytes > c->ws_bytes) return LS_EWORKSPACE;
     if (hipMemcpyAsync(dst_device, c->ws + off, bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)) != hipSuccess)

@@ -341,16 +341,19 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
 // ---- finish: add the two diagonal partials, reduce the total ------------------------------------
 // grid (B*Hq).  Diagonal o is met by keys n-w-o .. n-1-o (clipped at 0), i.e. by key blocks
 // kA = max(0, n-w-o)/SB and kB = (n-1-o)/SB, which are equal or adjacent.
+constexpr int FINISH_SPLIT = 8;            // workgroups per head (a head alone is a string of load round trips)
 __global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguous) {
     __shared__ float red[1024];
-    const int bh = blockIdx.x, tid = threadIdx.x;
+    const int bh = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
     const int64_t n = a.n;
+    const int64_t per = ((n + FINISH_SPLIT - 1) / FINISH_SPLIT + 1023) / 1024 * 1024;   // this workgroup's range, whole rounds of threads
+    const int64_t beg = (int64_t)part * per, end = beg + per < n ? beg + per : n;
     if (contiguous) {
-        for (int64_t o0 = tid; o0 < n; o0 += 8 * 1024) {       // eight diagonals per thread, all loads first
-            float sa[8], ma[8], sb[8], mb[8]; bool two[8];
+        for (int64_t o0 = beg + tid; o0 < end; o0 += 4 * 1024) {   // four diagonals per thread, all loads first
+            float sa[4], ma[4], sb[4], mb[4]; bool two[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int64_t o = o0 + j * 1024 < n ? o0 + j * 1024 : n - 1;
+            for (int j = 0; j < 4; ++j) {
+                const int64_t o = o0 + j * 1024 < end ? o0 + j * 1024 : end - 1;
                 int64_t lo = n - a.w - o; if (lo < 0) lo = 0;
                 const int64_t kA = lo / SB, kB = (n - 1 - o) / SB;
                 const float* pa = a.spart + (((kA & 1) * a.BH + bh) * n + o) * 2;
@@ -359,23 +362,23 @@ __global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguou
                 sa[j] = pa[0]; ma[j] = pa[1]; sb[j] = pb[0]; mb[j] = pb[1];
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < 4; ++j) {
                 const int64_t o = o0 + j * 1024;
-                if (o < n) {
+                if (o < end) {
                     a.slash[(int64_t)bh * n + o] = two[j] ? sa[j] + sb[j] : sa[j];      // lower key block first
                     a.smax[(int64_t)bh * n + o] = two[j] ? fmaxf(ma[j], mb[j]) : ma[j];
                 }
             }
         }
     }
-    // total = sum of the column sums, fixed tree order
+    // this range's share of total = sum of the column sums: per thread in index order, then a fixed tree
     float acc = 0.f;
-    for (int64_t i0 = tid; i0 < n; i0 += 8 * 1024) {           // same order of additions as one element per trip
-        float v8[8];
+    for (int64_t i0 = beg + tid; i0 < end; i0 += 4 * 1024) {
+        float v4[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { const int64_t i = i0 + j * 1024; v8[j] = i < n ? a.vert[(int64_t)bh * n + i] : 0.f; }
+        for (int j = 0; j < 4; ++j) { const int64_t i = i0 + j * 1024; v4[j] = i < end ? a.vert[(int64_t)bh * n + i] : 0.f; }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) if (i0 + j * 1024 < n) acc += v8[j];
+        for (int j = 0; j < 4; ++j) if (i0 + j * 1024 < end) acc += v4[j];
     }
     red[tid] = acc;
     __syncthreads();
@@ -383,7 +386,15 @@ __global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguou
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) a.total[bh] = red[0];
+    if (tid == 0) a.part[(int64_t)bh * FINISH_SPLIT + part] = red[0];   // `part` is free again once merge_kernel has run
+}
+
+// total[bh] = the ranges' shares added in a fixed tree order
+__global__ void total_kernel(ScoreArgs a) {
+    const int bh = blockIdx.x * blockDim.x + threadIdx.x;
+    if (bh >= a.BH) return;
+    const float* p = a.part + (int64_t)bh * FINISH_SPLIT;
+    a.total[bh] = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
 }
 
 __global__ void fill_zero_kernel(float* p, int64_t count) {
@@ -423,7 +434,8 @@ static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
         hipLaunchKernelGGL((lines_kernel<T, D, 2>), grid, dim3(SCORE_THREADS), smem, st, a);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(finish_kernel, dim3(a.BH), dim3(1024), 0, st, a, mode == 0 ? 1 : 0);
+    hipLaunchKernelGGL(finish_kernel, dim3(a.BH, FINISH_SPLIT), dim3(1024), 0, st, a, mode == 0 ? 1 : 0);
+    hipLaunchKernelGGL(total_kernel, dim3((a.BH + 255) / 256), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
