@@ -9,10 +9,11 @@
 //                 output position).  The sorted segments are then merged by rank: every element's
 //                 final position is its position in its segment plus, by bisection, the number of
 //                 elements of the other segments that precede it.
-//   walk_kernel   one walking wave per head: the greedy loop of Alg. 2 in binary32 with the operands and
-//                 operation order of the definition; runs of picks from one list are decided 64 at a
-//                 time by the lanes, the running sum is accumulated pick by pick.  A second wave
-//                 stages the sorted lists and their overlap prefix sums in LDS ahead of the walk.
+//   walk_kernel   one workgroup of four waves per head: the greedy loop of Alg. 2 in binary32 with the operands
+//                 and operation order of the definition.  One wave decides runs of up to 128 picks from one
+//                 list with its lanes, one accumulates the running sum pick by pick behind it and finds
+//                 the pick that reaches the target, and one wave per list stages the sorted list and its
+//                 overlap prefix sums in LDS ahead of both.
 //   emit_kernel   one workgroup per (head, list): the chosen prefix of a sorted list becomes an
 //                 ascending index list (bitmap in LDS + prefix popcount).
 //   topb_*        Alg. 3: the `budget` largest scores per KV head by a three-digit radix select on the
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 }
 
 // ---- the greedy loop ----------------------------------------------------------------------------
-// One workgroup of two waves per head.  The loop of Alg. 2 is sequential, but two things about it are not:
+// One workgroup of four waves per head.  The loop of Alg. 2 is sequential, but three things about it are not:
 //   * ol_s after k slashes were taken is the left-to-right binary32 sum of the first k maxima of
 //     the slash list, whatever the interleaving with verticals was (likewise ol_v), so both
 //     running overlaps are prefix arrays that can be filled ahead of the walk (still added one
@@ -203,136 +204,244 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 //   * while the walk keeps taking from one list, the state of the other list is frozen, so the
 //     next 64 ratio tests can be evaluated by the 64 lanes at once; a ballot gives the length of
 //     the run of equal decisions.
-// What stays sequential is the accumulation of `sum` with its exit test after every pick: one
-// add and one compare per pick, on values already sitting in the lanes' registers.
-// Each pick therefore sees exactly the operands, operation order and roundings of the definition.
-constexpr int WALK_THREADS = 128;              // wave 0 walks; wave 1 fills the list windows ahead of it
+//   * which list the next pick comes from does not depend on `sum`; only the end of the walk does.  So the
+//     decisions can run ahead of the sum: they are handed over run by run (the gain of every pick, in pick
+//     order) through a small ring in LDS, and whatever was decided beyond the pick that reaches the target
+//     is dropped.
+// What stays sequential are two chains of binary32 additions, one add per line each: the overlap prefix sums
+// and `sum` with its exit test after every pick.  Both are evaluated by a wave whose lanes hold consecutive
+// entries and pass the last partial sum to the right neighbour, one lane settling per pass, so every value is
+// the one the sequential loop would hold and each pick sees exactly the operands, operation order and
+// roundings of the definition.
+constexpr int WALK_THREADS = 256;              // wave 0 decides the runs, wave 2 sums, waves 1 and 3 fill the windows of a list each
 constexpr int WALK_WIN = 512;                  // window of a list kept in LDS
 constexpr int WALK_STRIDE = WALK_WIN - 128;    // window k of a list covers sorted positions [k * STRIDE, k * STRIDE + WIN)
-constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the two waves (never reached; about a second)
+constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the waves (never reached; about a second)
 
 // One window of one sorted list: weights, line lengths, largest entries, and pre[i] = the overlap sum
 // when the first k * STRIDE + i lines of the list have been taken.
 struct WalkWin { float cw[WALK_WIN], cl[WALK_WIN], cm[WALK_WIN], pre[WALK_WIN + 4]; };
-struct WalkSync { int ready[2], cur[2], done, err, pad[2]; };
-constexpr size_t WALK_LDS_BYTES = 4 * sizeof(WalkWin) + sizeof(WalkSync);
+// One run of picks from one list: the gain of each pick, how many of them count, and whether the walk ends
+// after them because no line is left that adds anything.
+struct WalkRun { float g[128]; int which, limit, last, pad; };
+struct WalkSync { int ready[2], cur[2], done, err, runs, summed, decided, stop, pad[2]; };
+constexpr int WALK_RING = 4;                   // runs decided ahead of the running sum
+constexpr size_t WALK_LDS_BYTES = 4 * sizeof(WalkWin) + WALK_RING * sizeof(WalkRun) + sizeof(WalkSync);
 
 __device__ __forceinline__ int walk_ld(const int* p) { return __builtin_amdgcn_readfirstlane(__atomic_load_n(p, __ATOMIC_RELAXED)); }
 __device__ __forceinline__ void walk_st(int* p, int v) { __atomic_store_n(p, v, __ATOMIC_RELAXED); }
 
+// pre[start + i] = acc + cm[start] + ... + cm[start + i - 1] (added left to right in binary32) for i < 64 * E, by
+// all lanes of a wave; returns the sum behind the last entry.  E is even, start a multiple of 2.
+template <int E>
+__device__ __forceinline__ float walk_scan(const float* cm, float* pre, int start, float acc, int lane) {
+    float m[E], x[E];
+    const float2* src = reinterpret_cast<const float2*>(cm + start + E * lane);
+#pragma unroll
+    for (int e = 0; e < E; e += 2) { const float2 t = src[e / 2]; m[e] = t.x; m[e + 1] = t.y; }
+    // lane 0 has no left neighbour: the shift hands it 0, and its first addend is acc + m[0], so it holds exactly that
+    const float addend0 = lane == 0 ? __fadd_rn(acc, m[0]) : m[0];
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = 0.f;
+    for (int p = 0; p < 64; p += 2) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                0, __builtin_bit_cast(int, x[E - 1]), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+            x[0] = __fadd_rn(left, addend0);
+#pragma unroll
+            for (int e = 1; e < E; ++e) x[e] = __fadd_rn(x[e - 1], m[e]);
+        }
+    }
+    const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        0, __builtin_bit_cast(int, x[E - 1]), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+    float2* dst = reinterpret_cast<float2*>(pre + start + E * lane);
+    dst[0] = make_float2(lane == 0 ? acc : left, x[0]);
+#pragma unroll
+    for (int e = 2; e < E; e += 2) dst[e / 2] = make_float2(x[e - 1], x[e]);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[E - 1]), 63));
+}
+
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
 //
-// The two waves share only LDS.  Wave 1 keeps two consecutive windows of each list resident
-// (window k goes to buffer k & 1): it produces window k of list l as soon as the walker's current
-// window of that list is >= k - 1, then publishes ready[l] = k + 1.  The walker publishes cur[l]
-// when it moves on to the next window, which frees the buffer of the one before.  Every wait is a
-// bounded spin; the walker ends both loops through `done`.
+// The waves share only LDS.  Waves 1 and 3 keep two consecutive windows of their list resident (window k goes
+// to buffer k & 1): window k of list l is produced as soon as the deciding wave's current window of that list
+// is >= k - 1, then ready[l] = k + 1 is published; the global loads of the window after it are issued before
+// its sums are added.  The deciding wave (0) publishes cur[l] when it moves on to the next window, which frees
+// the buffer of the one before, and runs = the number of runs it has put into the ring; the summing wave (2)
+// publishes summed = the number of runs it has taken out, and stop when the walk is over.  The summing wave
+// writes the result; the deciding wave ends the producers through `done`.  Every wait is a bounded spin that
+// also ends when another wave has reported a failed wait, so all four waves leave in every case.
 __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     extern __shared__ __align__(16) unsigned char walk_lds[];
     WalkWin (*win)[2] = reinterpret_cast<WalkWin (*)[2]>(walk_lds);          // [list][buffer]
-    WalkSync* sync = reinterpret_cast<WalkSync*>(walk_lds + 4 * sizeof(WalkWin));
+    WalkRun* ring = reinterpret_cast<WalkRun*>(walk_lds + 4 * sizeof(WalkWin));
+    WalkSync* sync = reinterpret_cast<WalkSync*>(walk_lds + 4 * sizeof(WalkWin) + WALK_RING * sizeof(WalkRun));
     const int bh = blockIdx.x, lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = (int)a.n;
     const int64_t nh = a.n_hat;
     const int64_t seg_s = ((int64_t)0 * a.BH + bh) * a.n, seg_v = ((int64_t)1 * a.BH + bh) * a.n;
 
-    if (threadIdx.x == 0) { sync->ready[0] = sync->ready[1] = 0; sync->cur[0] = sync->cur[1] = 0; sync->done = 0; sync->err = 0; }
+    if (threadIdx.x == 0) {
+        sync->ready[0] = sync->ready[1] = 0; sync->cur[0] = sync->cur[1] = 0; sync->done = 0; sync->err = 0;
+        sync->runs = 0; sync->summed = 0; sync->decided = 0; sync->stop = 0;
+    }
     __syncthreads();
 
-    if (wv == 1) {
-        // ------------------------------------------------------------------ window producer
-        const float* w_l[2] = {a.sorted_w + seg_s, a.sorted_w + seg_v};
-        const float* m_l[2] = {a.sorted_m + seg_s, a.sorted_m + seg_v};
-        const int32_t* i_l[2] = {a.sidx1 + seg_s, a.sidx1 + seg_v};
-        float carry[2] = {0.f, 0.f};           // overlap sum at the start of the next window of each list
-        int produced[2] = {0, 0};
+    if (wv == 1 || wv == 3) {
+        // ------------------------------------------------------------------ window producer of one list
+        const int l = wv == 1 ? 0 : 1;
+        const int64_t seg = l == 0 ? seg_s : seg_v;
+        const float* w_l = a.sorted_w + seg;
+        const float* m_l = a.sorted_m + seg;
+        const int32_t* i_l = a.sidx1 + seg;
+        const int nh32 = (int)nh;
+        constexpr int PER = WALK_WIN / 64;
+        float fw[PER], fm[PER]; int32_t fx[PER];           // the window after the last one written to LDS
+        auto fetch = [&](int k) {
+            const int base = k * WALK_STRIDE;
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const int gi = base + lane + j * 64;
+                const int gc = gi < n ? gi : n - 1;
+                fx[j] = i_l[gc]; fw[j] = w_l[gc]; fm[j] = m_l[gc];
+            }
+        };
+        fetch(0);
+        float acc = 0.f;                       // overlap sum behind the last entry scanned so far
+        int produced = 0;
         int spins = 0;
         while (walk_ld(&sync->done) == 0) {
-            bool need[2];
-#pragma unroll
-            for (int l = 0; l < 2; ++l)
-                need[l] = produced[l] < walk_ld(&sync->cur[l]) + 2 && (int64_t)produced[l] * WALK_STRIDE < n;
-            if (!need[0] && !need[1]) {
+            const bool need = produced < walk_ld(&sync->cur[l]) + 2 && (int64_t)produced * WALK_STRIDE < n;
+            if (!need) {
                 __builtin_amdgcn_s_sleep(2);
                 if (++spins > WALK_SPIN_LIMIT) { walk_st(&sync->err, 1); break; }
                 continue;
             }
             spins = 0;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            WalkWin& W = win[l][produced & 1];
+            const WalkWin& P = win[l][(produced & 1) ^ 1];     // the window before this one (still resident)
+            const int base = produced * WALK_STRIDE;
 #pragma unroll
-            for (int l = 0; l < 2; ++l) {
-                if (!need[l]) continue;
-                WalkWin& W = win[l][produced[l] & 1];
-                const int base = produced[l] * WALK_STRIDE;
-                // all loads of the window first (they are independent), then the LDS stores
-                constexpr int PER = WALK_WIN / 64;
-                float fw[PER], fm[PER]; int32_t fx[PER];
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    const int gi = base + lane + j * 64;
-                    const int gc = gi < n ? gi : n - 1;
-                    fx[j] = i_l[l][gc]; fw[j] = w_l[l][gc]; fm[j] = m_l[l][gc];
-                }
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    const int i = lane + j * 64;
-                    const bool in = base + i < n;
-                    const int64_t x = fx[j];
-                    W.cw[i] = in ? fw[j] : 0.f;
-                    W.cm[i] = in ? fm[j] : 0.f;
-                    W.cl[i] = in ? (float)((a.n - x) < nh ? (a.n - x) : nh) : 1.f;   // line length in the n_hat x n block
-                }
+            for (int j = 0; j < PER; ++j) {
+                const int i = lane + j * 64;
+                const bool in = base + i < n;
+                const int len = n - fx[j] < nh32 ? n - fx[j] : nh32;       // line length in the n_hat x n block
+                W.cw[i] = in ? fw[j] : 0.f;
+                W.cm[i] = in ? fm[j] : 0.f;
+                W.cl[i] = in ? (float)len : 1.f;
             }
+            // the first WIN - STRIDE entries are the last ones of the window before: their overlap sums are known
+            if (produced > 0) {
+#pragma unroll
+                for (int j = 0; j < (WALK_WIN - WALK_STRIDE) / 64; ++j)
+                    W.pre[lane + j * 64] = P.pre[WALK_STRIDE + lane + j * 64];
+            }
+            fetch(produced + 1);               // in flight while the sums below are added
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            float next_carry = 0.f;
-            if (lane < 2 && (lane == 0 ? need[0] : need[1])) {
-                // lane l scans list l: one add after the other, in list order; the next 16 maxima are read
-                // while the current 16 are added
-                WalkWin& W = win[lane][(lane == 0 ? produced[0] : produced[1]) & 1];
-                float acc = lane == 0 ? carry[0] : carry[1];
-                const f32x4* src = reinterpret_cast<const f32x4*>(W.cm);
-                float* dst = W.pre;
-                f32x4 cur[4], nxt[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) cur[q] = src[q];
-                for (int i = 0; i < WALK_WIN; i += 16) {
-                    const int ni = i + 16 < WALK_WIN ? i + 16 : i;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) nxt[q] = src[ni / 4 + q];
-                    if (i == WALK_STRIDE) next_carry = acc;            // STRIDE is a multiple of 16
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        f32x4 o;
-                        o.x = acc; acc = __fadd_rn(acc, cur[q].x);
-                        o.y = acc; acc = __fadd_rn(acc, cur[q].y);
-                        o.z = acc; acc = __fadd_rn(acc, cur[q].z);
-                        o.w = acc; acc = __fadd_rn(acc, cur[q].w);
-                        *reinterpret_cast<f32x4*>(dst + i + 4 * q) = o;
-                    }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
-                }
-                dst[WALK_WIN] = acc;
-            }
-            const float c0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, next_carry), 0));
-            const float c1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, next_carry), 1));
+            // The overlap sums of the new entries: one add after the other, in list order.  Lane j owns E consecutive
+            // entries; a pass is "take the last sum of the lane to the left, add my E maxima one after the other",
+            // and pass p settles lane p, so 64 passes leave every lane with the sums the sequential loop would
+            // hold (the lanes to the right of the settled ones compute values that the later passes replace).
+            if (produced == 0) acc = walk_scan<2>(W.cm, W.pre, 0, acc, lane);
+            acc = walk_scan<(WALK_STRIDE / 64)>(W.cm, W.pre, WALK_WIN - WALK_STRIDE, acc, lane);
+            if (lane == 0) W.pre[WALK_WIN] = acc;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
-            if (need[0]) { carry[0] = c0; ++produced[0]; if (lane == 0) walk_st(&sync->ready[0], produced[0]); }
-            if (need[1]) { carry[1] = c1; ++produced[1]; if (lane == 0) walk_st(&sync->ready[1], produced[1]); }
+            ++produced;
+            if (lane == 0) walk_st(&sync->ready[l], produced);
         }
         return;
     }
 
-    // ---------------------------------------------------------------------- the walk (wave 0)
-    const float target = a.alpha * a.total[bh];
+    if (wv == 2) {
+        // ------------------------------------------------------------------ the running sum
+        // Takes the runs in the order they were decided and adds their gains pick by pick; the first pick whose
+        // sum reaches the target ends the walk.
+        const float target = a.alpha * a.total[bh];
+        float sum = 0.f;
+        int cnt_s = 0, cnt_v = 0;              // lines taken from each list
+        int k = 0;                             // runs summed
+        bool failed = false, all = false;
+        while (sum < target) {
+            bool have = false;
+            int spins = 0;
+            for (;;) {
+                if (walk_ld(&sync->runs) > k) { have = true; break; }
+                if (walk_ld(&sync->decided)) {                       // stored after the last run was published
+                    have = walk_ld(&sync->runs) > k;
+                    failed = !have && walk_ld(&sync->err) != 0;
+                    break;
+                }
+                if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (!have) break;                  // both lists were used up (or a wait ran into its bound)
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            const WalkRun& R = ring[k & (WALK_RING - 1)];
+            const int which = __builtin_amdgcn_readfirstlane(R.which);
+            const int limit = __builtin_amdgcn_readfirstlane(R.limit);
+            const int last = __builtin_amdgcn_readfirstlane(R.last);
+            const float2 gn = *reinterpret_cast<const float2*>(&R.g[2 * lane]);
+            const float gain0 = gn.x, gain1 = gn.y;
+            // Lane j ends up with the running sums after its two picks: x0_j = x1_{j-1} + gain0_j, x1_j = x0_j + gain1_j,
+            // lane 0 starting from `sum`.  One pass of "take the left neighbour's x1, add my two gains one after the
+            // other" over all lanes settles one more lane, in order, so ceil(limit / 2) passes reproduce the
+            // pick-by-pick additions exactly; the first entry whose sum reaches the target is the pick the loop of
+            // the definition stops after.  (Lane 0 has no left neighbour: the shift hands it 0 and its first addend
+            // is sum + gain0, so it holds exactly that.)
+            const float addend0 = lane == 0 ? __fadd_rn(sum, gain0) : gain0;
+            float x0 = 0.f, x1 = 0.f;
+            for (int p0 = 0; p0 < limit; p0 += 8) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                        0, __builtin_bit_cast(int, x1), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+                    x0 = __fadd_rn(left, addend0);
+                    x1 = __fadd_rn(x0, gain1);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // the slot may be written again
+            ++k;
+            if (lane == 0) walk_st(&sync->summed, k);
+            // entries below `limit`: entry 0 of lane j is pick 2j, entry 1 is pick 2j + 1
+            const int n0 = (limit + 1) >> 1, n1 = limit >> 1;
+            const uint64_t lanes0 = n0 >= 64 ? ~0ull : ((1ull << n0) - 1ull);
+            const uint64_t lanes1 = n1 >= 64 ? ~0ull : ((1ull << n1) - 1ull);
+            const uint64_t h0 = __ballot(!(x0 < target)) & lanes0, h1 = __ballot(!(x1 < target)) & lanes1;
+            const int f0 = h0 ? 2 * (__ffsll((unsigned long long)h0) - 1) : 128;
+            const int f1 = h1 ? 2 * (__ffsll((unsigned long long)h1) - 1) + 1 : 128;
+            const int hit = f0 < f1 ? f0 : f1;
+            const bool reached = hit < 128;
+            const int taken = reached ? hit + 1 : limit;                    // picks applied
+            if (taken > 0) {
+                const float xs = ((taken - 1) & 1) ? x1 : x0;
+                sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xs), (taken - 1) >> 1));
+            }
+            cnt_s += which == 0 ? taken : 0;
+            cnt_v += which == 0 ? 0 : taken;
+            if (!reached && last) { all = true; break; }  // the pick after the last one has no positive gain
+        }
+        if (lane == 0) {
+            walk_st(&sync->stop, 1);
+            if (failed) walk_st(&sync->err, 1);
+            // a wait that ran into its bound (never observed) reports an empty selection
+            a.s_cnt[bh] = failed ? 0 : all ? n : cnt_s;
+            a.v_cnt[bh] = failed ? 0 : all ? n : cnt_v;
+            if (a.accounted) a.accounted[bh] = sum;
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- the decisions (wave 0)
     const bool early = a.accounted == nullptr;
-    int head[2] = {0, 0};                      // is, iv
-    int curw[2] = {0, 0};                      // window of each list the heads are in
-    float sum = 0.f;
+    int is = 0, iv = 0;                        // heads of the two lists (plain scalars: an array indexed by the
+    int cur_s = 0, cur_v = 0;                  // list would be kept in scratch memory); window each head is in
+    int published = 0;                         // runs handed to the summing wave
     bool failed = false;
 
     auto wait_ready = [&](int l, int k) {      // until window k of list l is resident
@@ -348,13 +457,12 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
 
     // What the lanes need of a list when its head is at `h`: lane l looks at the entries h + 2l and h + 2l + 1
     // (weight, overlap prefix, length), every lane at the head's own three values.  Re-read only when the head of
-    // that list moves; the read for the head position after the current run is issued before the run's sums are
-    // settled, so its LDS latency hides behind them.  (A window holds WALK_WIN entries from a start that is at
-    // most WALK_STRIDE - 1 before the head: the 128 entries after the head are always inside it.)
+    // that list moves.  (A window holds WALK_WIN entries from a start that is at most WALK_STRIDE - 1 before
+    // the head: the 128 entries after the head are always inside it.)
     struct View { float cw[2], pre[2], cl[2], w0, l0, ol0; bool ok[2], has; };
-    auto view = [&](int l, int h) {
-        const WalkWin& W = win[l][curw[l] & 1];
-        const int base = curw[l] * WALK_STRIDE;
+    auto view = [&](int l, int h, int cw) {
+        const WalkWin& W = win[l][cw & 1];
+        const int base = cw * WALK_STRIDE;
         View r;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -370,7 +478,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         r.ol0 = W.pre[h - base];
         return r;
     };
-    View S = view(0, 0), V = view(1, 0);
+    View S = view(0, 0, 0), V = view(1, 0, 0);
     // position of the first set bit in the order entry 0 of lane 0, entry 1 of lane 0, entry 0 of lane 1, ...
     // (128 if neither mask has one)
     auto first_of = [](uint64_t m0, uint64_t m1) -> int {
@@ -380,24 +488,23 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     };
 
     while (!failed) {
-        const int is = head[0], iv = head[1];
-        if (!(sum < target) || (is >= n && iv >= n)) break;
+        if ((is >= n && iv >= n) || walk_ld(&sync->stop)) break;
         // move on to the next window of a list once its head has reached that window's start
-        if (is < n && is >= (curw[0] + 1) * WALK_STRIDE) {
-            ++curw[0];
+        if (is < n && is >= (cur_s + 1) * WALK_STRIDE) {
+            ++cur_s;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the window left behind
-            if (lane == 0) walk_st(&sync->cur[0], curw[0]);
-            wait_ready(0, curw[0]);
+            if (lane == 0) walk_st(&sync->cur[0], cur_s);
+            wait_ready(0, cur_s);
             if (failed) break;
-            S = view(0, is);
+            S = view(0, is, cur_s);
         }
-        if (iv < n && iv >= (curw[1] + 1) * WALK_STRIDE) {
-            ++curw[1];
+        if (iv < n && iv >= (cur_v + 1) * WALK_STRIDE) {
+            ++cur_v;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            if (lane == 0) walk_st(&sync->cur[1], curw[1]);
-            wait_ready(1, curw[1]);
+            if (lane == 0) walk_st(&sync->cur[1], cur_v);
+            wait_ready(1, cur_v);
             if (failed) break;
-            V = view(1, iv);
+            V = view(1, iv, cur_v);
         }
         const bool s_has = S.has, v_has = V.has;
         // entry e of lane j: the decision if the walk has taken 2j + e more slashes (iv frozen)
@@ -433,53 +540,35 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             run = first_of(~__ballot(take[0]), ~__ballot(take[1]));
         }
         if (run == 0) break;                   // cannot happen (entry 0 of lane 0 repeats the head's test); never spin
-        // picks 0 .. run-1 come from list `which`; stop early when no head has a positive gain
+        // picks 0 .. run-1 come from list `which`; the walk ends early at a pick with no positive gain left
         int stop_dead = 128;
         if (early) stop_dead = first_of(__ballot(dead[0]), __ballot(dead[1]));
-        // picks 0 .. limit-1 are applied; the running sum is accumulated pick by pick
         const int limit = run < stop_dead ? run : stop_dead;
-        // the list's view after the run (used only if the whole run is applied and the walk goes on; a
-        // window change re-reads it)
-        const View nxt = view(which, head[which] + limit);
-        // Lane j ends up with the running sums after its two picks: x0_j = x1_{j-1} + gain0_j, x1_j = x0_j + gain1_j,
-        // lane 0 starting from `sum`.  One pass of "take the left neighbour's x1, add my two gains one after the
-        // other" over all lanes settles one more lane, in order, so ceil(limit / 2) passes reproduce the
-        // pick-by-pick additions exactly; the first entry whose sum reaches the target is the pick the loop of
-        // the definition stops after.  (Lane 0 has no left neighbour: the shift hands it 0 and its first addend
-        // is sum + gain0, so it holds exactly that.)
-        const float addend0 = lane == 0 ? __fadd_rn(sum, gain[0]) : gain[0];
-        float x0 = 0.f, x1 = 0.f;
-        for (int p0 = 0; p0 < limit; p0 += 8) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
-                    0, __builtin_bit_cast(int, x1), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
-                x0 = __fadd_rn(left, addend0);
-                x1 = __fadd_rn(x0, gain[1]);
-            }
+        const View nxt = view(which, (which == 0 ? is : iv) + limit, which == 0 ? cur_s : cur_v);
+        // hand the run over: a free slot of the ring, the gains, then the count of published runs
+        bool stopped = false;
+        int spins = 0;
+        while (published - walk_ld(&sync->summed) >= WALK_RING) {
+            if (walk_ld(&sync->stop)) { stopped = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
         }
-        // entries below `limit`: entry 0 of lane j is pick 2j, entry 1 is pick 2j + 1
-        const int n0 = (limit + 1) >> 1, n1 = limit >> 1;
-        const uint64_t lanes0 = n0 >= 64 ? ~0ull : ((1ull << n0) - 1ull);
-        const uint64_t lanes1 = n1 >= 64 ? ~0ull : ((1ull << n1) - 1ull);
-        const int hit = first_of(__ballot(!(x0 < target)) & lanes0, __ballot(!(x1 < target)) & lanes1);
-        const bool reached = hit < 128;
-        const int taken = reached ? hit + 1 : limit;                    // picks applied
-        if (taken > 0) {
-            const float xs = ((taken - 1) & 1) ? x1 : x0;
-            sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xs), (taken - 1) >> 1));
-        }
-        const bool exhausted = !reached && stop_dead < run;      // the pick after the last one has no positive gain
-        head[which] += taken;
-        if (exhausted) { head[0] = n; head[1] = n; break; }
-        if (which == 0) S = nxt; else V = nxt;
+        if (stopped || failed) break;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        WalkRun& R = ring[published & (WALK_RING - 1)];
+        *reinterpret_cast<float2*>(&R.g[2 * lane]) = make_float2(gain[0], gain[1]);
+        if (lane == 0) { R.which = which; R.limit = limit; R.last = stop_dead < run ? 1 : 0; }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        ++published;
+        if (lane == 0) walk_st(&sync->runs, published);
+        if (stop_dead < run) break;            // nothing after this run can add to the sum
+        if (which == 0) { is += limit; S = nxt; } else { iv += limit; V = nxt; }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     if (lane == 0) {
+        if (failed) walk_st(&sync->err, 1);
+        walk_st(&sync->decided, 1);
         walk_st(&sync->done, 1);
-        // a wait that ran into its bound (never observed) reports an empty selection
-        a.s_cnt[bh] = failed ? 0 : head[0];
-        a.v_cnt[bh] = failed ? 0 : head[1];
-        if (a.accounted) a.accounted[bh] = sum;
     }
 }
 
