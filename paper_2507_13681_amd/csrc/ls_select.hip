@@ -10,7 +10,7 @@
 //                 final position is its position in its segment plus, by bisection, the number of
 //                 elements of the other segments that precede it.
 //   walk_kernel   one workgroup of four waves per head: the greedy loop of Alg. 2 in binary32 with the operands
-//                 and operation order of the definition.  One wave decides runs of up to 128 picks from one
+//                 and operation order of the definition.  One wave decides runs of up to 512 picks from one
 //                 list with its lanes, one accumulates the running sum pick by pick behind it and finds
 //                 the pick that reaches the target, and one wave per list stages the sorted list and its
 //                 overlap prefix sums in LDS ahead of both.
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
     const float* src = (list == 0 ? a.slash : a.vert) + (int64_t)bh * n + base0;
     const int64_t out0 = ((int64_t)list * a.BH + bh) * n + base0;
     // slots past the end of the list hold the largest key: they sort behind every element and, being
-    // the highest local indices, stay behind equal keys as well
+    // the highest local indices, turn behind equal keys as well
     for (int i = tid; i < SORT_SEG; i += SORT_THREADS) {
         kb0[i] = i < cnt ? desc_key(src[i]) : 0xFFFFFFFFu;
         ib0[i] = (uint16_t)i;
@@ -214,8 +214,11 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 // the one the sequential loop would hold and each pick sees exactly the operands, operation order and
 // roundings of the definition.
 constexpr int WALK_THREADS = 256;              // wave 0 decides the runs, wave 2 sums, waves 1 and 3 fill the windows of a list each
-constexpr int WALK_WIN = 512;                  // window of a list kept in LDS
-constexpr int WALK_STRIDE = WALK_WIN - 128;    // window k of a list covers sorted positions [k * STRIDE, k * STRIDE + WIN)
+constexpr int WALK_E = 8;                      // consecutive list entries a lane looks at: a run has up to 64 * E picks
+constexpr int WALK_RUN = 64 * WALK_E;
+constexpr int WALK_WIN = 3 * WALK_RUN;         // window of a list kept in LDS
+constexpr int WALK_STRIDE = WALK_WIN - WALK_RUN;   // window k of a list covers sorted positions [k * STRIDE, k * STRIDE + WIN)
+static_assert(WALK_E % 2 == 0 && WALK_STRIDE % 128 == 0 && WALK_STRIDE > 0, "walk_scan wants even entry counts per lane");
 constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the waves (never reached; about a second)
 
 // One window of one sorted list: weights, line lengths, largest entries, and pre[i] = the overlap sum
@@ -223,7 +226,7 @@ constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between th
 struct WalkWin { float cw[WALK_WIN], cl[WALK_WIN], cm[WALK_WIN], pre[WALK_WIN + 4]; };
 // One run of picks from one list: the gain of each pick, how many of them count, and whether the walk ends
 // after them because no line is left that adds anything.
-struct WalkRun { float g[128]; int which, limit, last, pad; };
+struct WalkRun { float g[WALK_RUN]; int which, limit, last, pad; };
 struct WalkSync { int ready[2], cur[2], done, err, runs, summed, decided, stop, pad[2]; };
 constexpr int WALK_RING = 4;                   // runs decided ahead of the running sum
 constexpr size_t WALK_LDS_BYTES = 4 * sizeof(WalkWin) + WALK_RING * sizeof(WalkRun) + sizeof(WalkSync);
@@ -260,6 +263,18 @@ __device__ __forceinline__ float walk_scan(const float* cm, float* pre, int star
 #pragma unroll
     for (int e = 2; e < E; e += 2) dst[e / 2] = make_float2(x[e - 1], x[e]);
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[E - 1]), 63));
+}
+
+// Position of the first set bit in the order entry 0 of lane 0, entry 1 of lane 0, ..., entry 0 of lane 1, ...
+// where m[e] has bit j set for entry e of lane j (WALK_RUN if no mask has one).
+__device__ __forceinline__ int walk_first(const uint64_t (&m)[WALK_E]) {
+    int f = WALK_RUN;
+#pragma unroll
+    for (int e = 0; e < WALK_E; ++e) {
+        const int fe = m[e] ? WALK_E * (__ffsll((unsigned long long)m[e]) - 1) + e : WALK_RUN;
+        f = fe < f ? fe : f;
+    }
+    return f;
 }
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
@@ -347,7 +362,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             // entries; a pass is "take the last sum of the lane to the left, add my E maxima one after the other",
             // and pass p settles lane p, so 64 passes leave every lane with the sums the sequential loop would
             // hold (the lanes to the right of the settled ones compute values that the later passes replace).
-            if (produced == 0) acc = walk_scan<2>(W.cm, W.pre, 0, acc, lane);
+            if (produced == 0) acc = walk_scan<WALK_E>(W.cm, W.pre, 0, acc, lane);
             acc = walk_scan<(WALK_STRIDE / 64)>(W.cm, W.pre, WALK_WIN - WALK_STRIDE, acc, lane);
             if (lane == 0) W.pre[WALK_WIN] = acc;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -386,41 +401,51 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             const int which = __builtin_amdgcn_readfirstlane(R.which);
             const int limit = __builtin_amdgcn_readfirstlane(R.limit);
             const int last = __builtin_amdgcn_readfirstlane(R.last);
-            const float2 gn = *reinterpret_cast<const float2*>(&R.g[2 * lane]);
-            const float gain0 = gn.x, gain1 = gn.y;
-            // Lane j ends up with the running sums after its two picks: x0_j = x1_{j-1} + gain0_j, x1_j = x0_j + gain1_j,
-            // lane 0 starting from `sum`.  One pass of "take the left neighbour's x1, add my two gains one after the
-            // other" over all lanes settles one more lane, in order, so ceil(limit / 2) passes reproduce the
-            // pick-by-pick additions exactly; the first entry whose sum reaches the target is the pick the loop of
-            // the definition stops after.  (Lane 0 has no left neighbour: the shift hands it 0 and its first addend
-            // is sum + gain0, so it holds exactly that.)
-            const float addend0 = lane == 0 ? __fadd_rn(sum, gain0) : gain0;
-            float x0 = 0.f, x1 = 0.f;
-            for (int p0 = 0; p0 < limit; p0 += 8) {
+            float g[WALK_E], x[WALK_E];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+            for (int e = 0; e < WALK_E; e += 2) {
+                const float2 t = *reinterpret_cast<const float2*>(&R.g[WALK_E * lane + e]);
+                g[e] = t.x; g[e + 1] = t.y;
+            }
+            // Lane j ends up with the running sums after its E picks: x[0] = (x[E-1] of lane j-1) + g[0], x[e] =
+            // x[e-1] + g[e], lane 0 starting from `sum`.  One pass of "take the left neighbour's last sum, add my
+            // gains one after the other" over all lanes settles one more lane, in order, so ceil(limit / E) passes
+            // reproduce the pick-by-pick additions exactly; the first entry whose sum reaches the target is the
+            // pick the loop of the definition stops after.  (Lane 0 has no left neighbour: the shift hands it 0 and
+            // its first addend is sum + g[0], so it holds exactly that.)
+            const float addend0 = lane == 0 ? __fadd_rn(sum, g[0]) : g[0];
+#pragma unroll
+            for (int e = 0; e < WALK_E; ++e) x[e] = 0.f;
+            for (int p0 = 0; p0 < limit; p0 += 2 * WALK_E) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
                     const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
-                        0, __builtin_bit_cast(int, x1), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
-                    x0 = __fadd_rn(left, addend0);
-                    x1 = __fadd_rn(x0, gain1);
+                        0, __builtin_bit_cast(int, x[WALK_E - 1]), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+                    x[0] = __fadd_rn(left, addend0);
+#pragma unroll
+                    for (int e = 1; e < WALK_E; ++e) x[e] = __fadd_rn(x[e - 1], g[e]);
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // the slot may be written again
             ++k;
             if (lane == 0) walk_st(&sync->summed, k);
-            // entries below `limit`: entry 0 of lane j is pick 2j, entry 1 is pick 2j + 1
-            const int n0 = (limit + 1) >> 1, n1 = limit >> 1;
-            const uint64_t lanes0 = n0 >= 64 ? ~0ull : ((1ull << n0) - 1ull);
-            const uint64_t lanes1 = n1 >= 64 ? ~0ull : ((1ull << n1) - 1ull);
-            const uint64_t h0 = __ballot(!(x0 < target)) & lanes0, h1 = __ballot(!(x1 < target)) & lanes1;
-            const int f0 = h0 ? 2 * (__ffsll((unsigned long long)h0) - 1) : 128;
-            const int f1 = h1 ? 2 * (__ffsll((unsigned long long)h1) - 1) + 1 : 128;
-            const int hit = f0 < f1 ? f0 : f1;
-            const bool reached = hit < 128;
+            // entry e of lane j is pick E * j + e; only picks below `limit` count
+            uint64_t hm[WALK_E];
+#pragma unroll
+            for (int e = 0; e < WALK_E; ++e) {
+                const int ne = (limit - e + WALK_E - 1) / WALK_E;       // lanes whose entry e is below limit
+                const uint64_t lanes = ne >= 64 ? ~0ull : ne <= 0 ? 0ull : ((1ull << ne) - 1ull);
+                hm[e] = __ballot(!(x[e] < target)) & lanes;
+            }
+            const int hit = walk_first(hm);
+            const bool reached = hit < WALK_RUN;
             const int taken = reached ? hit + 1 : limit;                    // picks applied
             if (taken > 0) {
-                const float xs = ((taken - 1) & 1) ? x1 : x0;
-                sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xs), (taken - 1) >> 1));
+                const int te = (taken - 1) % WALK_E;
+                float xs = x[0];
+#pragma unroll
+                for (int e = 1; e < WALK_E; ++e) xs = te == e ? x[e] : xs;
+                sum = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xs), (taken - 1) / WALK_E));
             }
             cnt_s += which == 0 ? taken : 0;
             cnt_v += which == 0 ? 0 : taken;
@@ -455,18 +480,18 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     wait_ready(0, 0);
     wait_ready(1, 0);
 
-    // What the lanes need of a list when its head is at `h`: lane l looks at the entries h + 2l and h + 2l + 1
+    // What the lanes need of a list when its head is at `h`: lane l looks at the entries h + E l .. h + E l + E - 1
     // (weight, overlap prefix, length), every lane at the head's own three values.  Re-read only when the head of
     // that list moves.  (A window holds WALK_WIN entries from a start that is at most WALK_STRIDE - 1 before
-    // the head: the 128 entries after the head are always inside it.)
-    struct View { float cw[2], pre[2], cl[2], w0, l0, ol0; bool ok[2], has; };
+    // the head: the 64 E entries after the head are always inside it.)
+    struct View { float cw[WALK_E], pre[WALK_E], cl[WALK_E], w0, l0, ol0; bool ok[WALK_E], has; };
     auto view = [&](int l, int h, int cw) {
         const WalkWin& W = win[l][cw & 1];
         const int base = cw * WALK_STRIDE;
         View r;
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int i = h + 2 * lane + e;
+        for (int e = 0; e < WALK_E; ++e) {
+            const int i = h + WALK_E * lane + e;
             r.ok[e] = i < n && (i - base) < WALK_WIN;
             const int ii = r.ok[e] ? i - base : 0;
             r.cw[e] = W.cw[ii]; r.pre[e] = W.pre[ii]; r.cl[e] = W.cl[ii];
@@ -479,14 +504,6 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         return r;
     };
     View S = view(0, 0, 0), V = view(1, 0, 0);
-    // position of the first set bit in the order entry 0 of lane 0, entry 1 of lane 0, entry 0 of lane 1, ...
-    // (128 if neither mask has one)
-    auto first_of = [](uint64_t m0, uint64_t m1) -> int {
-        const int f0 = m0 ? 2 * (__ffsll((unsigned long long)m0) - 1) : 128;
-        const int f1 = m1 ? 2 * (__ffsll((unsigned long long)m1) - 1) + 1 : 128;
-        return f0 < f1 ? f0 : f1;
-    };
-
     while (!failed) {
         if ((is >= n && iv >= n) || walk_ld(&sync->stop)) break;
         // move on to the next window of a list once its head has reached that window's start
@@ -507,42 +524,42 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             V = view(1, iv, cur_v);
         }
         const bool s_has = S.has, v_has = V.has;
-        // entry e of lane j: the decision if the walk has taken 2j + e more slashes (iv frozen)
-        float gain[2];
-        bool take[2], dead[2];
+        // entry e of lane j: the decision if the walk has taken E j + e more slashes (iv frozen)
+        float gain[WALK_E];
+        uint64_t turn[WALK_E], dead[WALK_E];       // ballots: the pick goes to the other list; no gain is left
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int i = is + 2 * lane + e;
+        for (int e = 0; e < WALK_E; ++e) {
+            const int i = is + WALK_E * lane + e;
             const float ds = __fsub_rn(S.cw[e], V.ol0);
             const float dv = __fsub_rn(V.w0, S.pre[e]);
             float cs = __fsub_rn(S.cl[e], (float)iv); if (cs < 1.0f) cs = 1.0f;
             float cv = __fsub_rn(V.l0, (float)i); if (cv < 1.0f) cv = 1.0f;
-            take[e] = S.ok[e] && (!v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));
-            dead[e] = !(ds > 0.f) && (!v_has || !(dv > 0.f));
+            turn[e] = ~__ballot(S.ok[e] && (!v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs)));
+            dead[e] = __ballot(!(ds > 0.f) && (!v_has || !(dv > 0.f)));
             gain[e] = ds;
         }
-        int run = first_of(~__ballot(take[0]), ~__ballot(take[1]));
+        int run = walk_first(turn);
         int which = 0;
         if (run == 0) {
-            // the head pick is a vertical; entry e of lane j: the decision if 2j + e more verticals are taken (is frozen)
+            // the head pick is a vertical; entry e of lane j: the decision if E j + e more verticals are taken (is frozen)
             which = 1;
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int i = iv + 2 * lane + e;
+            for (int e = 0; e < WALK_E; ++e) {
+                const int i = iv + WALK_E * lane + e;
                 const float dv = __fsub_rn(V.cw[e], S.ol0);
                 const float ds = __fsub_rn(S.w0, V.pre[e]);
                 float cv = __fsub_rn(V.cl[e], (float)is); if (cv < 1.0f) cv = 1.0f;
                 float cs = __fsub_rn(S.l0, (float)i); if (cs < 1.0f) cs = 1.0f;
-                take[e] = V.ok[e] && !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs));      // true: vertical again
-                dead[e] = !(dv > 0.f) && (!s_has || !(ds > 0.f));
+                turn[e] = ~__ballot(V.ok[e] && !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs)));   // set: not a vertical again
+                dead[e] = __ballot(!(dv > 0.f) && (!s_has || !(ds > 0.f)));
                 gain[e] = dv;
             }
-            run = first_of(~__ballot(take[0]), ~__ballot(take[1]));
+            run = walk_first(turn);
         }
         if (run == 0) break;                   // cannot happen (entry 0 of lane 0 repeats the head's test); never spin
         // picks 0 .. run-1 come from list `which`; the walk ends early at a pick with no positive gain left
-        int stop_dead = 128;
-        if (early) stop_dead = first_of(__ballot(dead[0]), __ballot(dead[1]));
+        int stop_dead = WALK_RUN;
+        if (early) stop_dead = walk_first(dead);
         const int limit = run < stop_dead ? run : stop_dead;
         const View nxt = view(which, (which == 0 ? is : iv) + limit, which == 0 ? cur_s : cur_v);
         // hand the run over: a free slot of the ring, the gains, then the count of published runs
@@ -556,7 +573,9 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         if (stopped || failed) break;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         WalkRun& R = ring[published & (WALK_RING - 1)];
-        *reinterpret_cast<float2*>(&R.g[2 * lane]) = make_float2(gain[0], gain[1]);
+#pragma unroll
+        for (int e = 0; e < WALK_E; e += 2)
+            *reinterpret_cast<float2*>(&R.g[WALK_E * lane + e]) = make_float2(gain[e], gain[e + 1]);
         if (lane == 0) { R.which = which; R.limit = limit; R.last = stop_dead < run ? 1 : 0; }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         ++published;
