@@ -2,7 +2,7 @@
 //
 //   sort_seg_kernel / sort_merge_kernel
 //                 Desc_Sort: the n line weights of a list in descending order, equal weights in
-//                 ascending index order.  Segments of 8192 elements are sorted inside LDS by a stable
+//                 ascending index order.  Segments of 2048 to 8192 elements are sorted inside LDS by a stable
 //                 LSD radix sort (4 x 8 bits): each of the 16 waves owns a contiguous slice, counts its
 //                 digits in its own histogram, and scatters its slice in order (ranks among equal
 //                 digits from wave ballots and the wave's running counters; no atomics decide an
@@ -38,35 +38,37 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {
 
 constexpr int SORT_THREADS = 1024;
 constexpr int SORT_WAVES = 16;
-constexpr int SORT_SEG = 8192;                 // elements one workgroup sorts inside LDS
-constexpr int SORT_SLICE = SORT_SEG / SORT_WAVES;
-constexpr size_t SORT_LDS_BYTES = 2 * SORT_SEG * 4 + 2 * SORT_SEG * 2 + SORT_WAVES * 256 * 4 + 256 * 4;
+constexpr int SORT_SEG_MAX = 8192;             // most elements one workgroup sorts inside LDS
+constexpr int SORT_SEG_MIN = 2048;
+constexpr size_t sort_lds_bytes(int seg) { return (size_t)2 * seg * 4 + (size_t)2 * seg * 2 + SORT_WAVES * 256 * 4 + 256 * 4; }
 
 // grid (segments, 2, BH): list 0 = diagonals (slash), 1 = columns (vert).  Sorts elements
-// [seg * SORT_SEG, +SORT_SEG) of one list entirely in LDS and writes the sorted keys (skey0) and their
+// [seg * SEG, +SEG) of one list entirely in LDS and writes the sorted keys (skey0) and their
 // line indices (sidx0) back to the same range.
+template <int SEG>
 __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
+    constexpr int SLICE = SEG / SORT_WAVES;
     extern __shared__ __align__(16) unsigned char sort_lds[];
     uint32_t* kb0 = reinterpret_cast<uint32_t*>(sort_lds);
-    uint32_t* kb1 = kb0 + SORT_SEG;
-    uint16_t* ib0 = reinterpret_cast<uint16_t*>(kb1 + SORT_SEG);
-    uint16_t* ib1 = ib0 + SORT_SEG;
-    uint32_t (*hist)[256] = reinterpret_cast<uint32_t (*)[256]>(ib1 + SORT_SEG);
+    uint32_t* kb1 = kb0 + SEG;
+    uint16_t* ib0 = reinterpret_cast<uint16_t*>(kb1 + SEG);
+    uint16_t* ib1 = ib0 + SEG;
+    uint32_t (*hist)[256] = reinterpret_cast<uint32_t (*)[256]>(ib1 + SEG);
     uint32_t* dbase = &hist[SORT_WAVES][0];
     const int seg = blockIdx.x, list = blockIdx.y, bh = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int64_t n = a.n;
-    const int64_t base0 = (int64_t)seg * SORT_SEG;
-    const int cnt = (int)(n - base0 < SORT_SEG ? n - base0 : SORT_SEG);
+    const int64_t base0 = (int64_t)seg * SEG;
+    const int cnt = (int)(n - base0 < SEG ? n - base0 : SEG);
     const float* src = (list == 0 ? a.slash : a.vert) + (int64_t)bh * n + base0;
     const int64_t out0 = ((int64_t)list * a.BH + bh) * n + base0;
     // slots past the end of the list hold the largest key: they sort behind every element and, being
     // the highest local indices, turn behind equal keys as well
-    for (int i = tid; i < SORT_SEG; i += SORT_THREADS) {
+    for (int i = tid; i < SEG; i += SORT_THREADS) {
         kb0[i] = i < cnt ? desc_key(src[i]) : 0xFFFFFFFFu;
         ib0[i] = (uint16_t)i;
     }
-    const int lo = wv * SORT_SLICE;
+    const int lo = wv * SLICE;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 8 * pass;
         const uint32_t* kin = (pass & 1) ? kb1 : kb0;
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
         uint16_t* iout = (pass & 1) ? ib0 : ib1;
         for (int i = tid; i < SORT_WAVES * 256; i += SORT_THREADS) (&hist[0][0])[i] = 0u;
         __syncthreads();
-        for (int i = lo + lane; i < lo + SORT_SLICE; i += 64) atomicAdd(&hist[wv][(kin[i] >> shift) & 255u], 1u);
+        for (int i = lo + lane; i < lo + SLICE; i += 64) atomicAdd(&hist[wv][(kin[i] >> shift) & 255u], 1u);
         __syncthreads();
         // exclusive offsets in (digit, wave) order
         if (tid < 256) {
@@ -103,27 +105,35 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
         __syncthreads();
         // in-order scatter of this wave's slice: inside a 64-element chunk the rank among equal digits
         // comes from wave ballots, across chunks from the wave's running counters
-        volatile uint32_t* myh = hist[wv];
+        // (the wave's counters are read and written with relaxed atomics: plain LDS accesses that the compiler keeps
+        // in program order around the wave barriers; a volatile pointer would turn them into flat accesses)
+        uint32_t* myh = hist[wv];
+        uint32_t keys[SLICE / 64]; uint16_t idxs[SLICE / 64];    // the slice is only read during the scatter
 #pragma unroll
-        for (int c = 0; c < SORT_SLICE / 64; ++c) {
-            const int i = lo + 64 * c + lane;
-            const uint32_t key = kin[i];
-            const uint16_t idx = iin[i];
+        for (int c = 0; c < SLICE / 64; ++c) { keys[c] = kin[lo + 64 * c + lane]; idxs[c] = iin[lo + 64 * c + lane]; }
+#pragma unroll
+        for (int c = 0; c < SLICE / 64; ++c) {
+            const uint32_t key = keys[c];
+            const uint16_t idx = idxs[c];
             const uint32_t dg = (key >> shift) & 255u;
-            uint64_t peers = ~0ull;
+            // lanes whose digit differs from mine in some bit: bit b of the lanes' digits as a wave mask, against
+            // my own bit b spread over a word
+            uint32_t diff_lo = 0u, diff_hi = 0u;
 #pragma unroll
             for (int bit = 0; bit < 8; ++bit) {
-                const bool one = (dg >> bit) & 1u;
-                const uint64_t bal = __ballot(one);
-                peers &= one ? bal : ~bal;
+                const int32_t m = (int32_t)(dg << (31 - bit)) >> 31;               // 0 or ~0
+                const uint64_t bal = __ballot(m != 0);
+                diff_lo |= (uint32_t)bal ^ (uint32_t)m;
+                diff_hi |= (uint32_t)(bal >> 32) ^ (uint32_t)m;
             }
+            const uint64_t peers = ~(((uint64_t)diff_hi << 32) | diff_lo);
             const uint64_t below = peers & ((1ull << lane) - 1ull);
             const uint32_t rank = __popcll(below);
-            const uint32_t pos = myh[dg] + rank;
+            const uint32_t pos = __atomic_load_n(&myh[dg], __ATOMIC_RELAXED) + rank;
             __builtin_amdgcn_wave_barrier();
             kout[pos] = key;
             iout[pos] = idx;
-            if (below == 0ull) myh[dg] = pos + (uint32_t)__popcll(peers);
+            if (below == 0ull) __atomic_store_n(&myh[dg], pos + (uint32_t)__popcll(peers), __ATOMIC_RELAXED);
             __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();                                   // every wave is done with the counters and the input buffer
@@ -138,53 +148,77 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
 // grid (segments, 2, BH).  Final position of an element of segment q = its position inside q + the
 // number of elements of every other segment that go before it: smaller key, or equal key in a segment
 // of smaller line indices (the order stays stable).  The other segments' sorted keys are staged in
-// LDS one at a time and searched by bisection.  Writes the sorted weights, line indices (sidx1) and
-// each line's largest entry.
-constexpr int MERGE_PER = SORT_SEG / SORT_THREADS;
+// LDS one at a time (two buffers: the next segment is loaded while the current one is searched) and
+// searched by bisection.  Writes the sorted weights, line indices (sidx1) and each line's largest entry.
+// Dynamic LDS: 2 * SEG keys.
+template <int SEG>
 __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) {
-    __shared__ uint32_t other[SORT_SEG];
+    constexpr int PER = SEG / SORT_THREADS;
+    extern __shared__ __align__(16) unsigned char merge_lds[];
+    uint32_t (*other)[SEG] = reinterpret_cast<uint32_t (*)[SEG]>(merge_lds);
     const int seg = blockIdx.x, list = blockIdx.y, bh = blockIdx.z;
     const int tid = threadIdx.x;
     const int64_t n = a.n;
-    const int nseg = (int)((n + SORT_SEG - 1) / SORT_SEG);
+    const int nseg = (int)((n + SEG - 1) / SEG);
     const int64_t lbase = ((int64_t)list * a.BH + bh) * n;
-    const int64_t base0 = (int64_t)seg * SORT_SEG;
-    const int cnt = (int)(n - base0 < SORT_SEG ? n - base0 : SORT_SEG);
-    uint32_t key[MERGE_PER]; uint32_t rank[MERGE_PER];
+    const int64_t base0 = (int64_t)seg * SEG;
+    const int cnt = (int)(n - base0 < SEG ? n - base0 : SEG);
+    uint32_t key[PER], rank[PER], nxt[PER];
+    auto fetch = [&](int q) {                               // keys of segment q, padded with the largest key
+        const int64_t qb = (int64_t)q * SEG;
+        const int qc = (int)(n - qb < SEG ? n - qb : SEG);
 #pragma unroll
-    for (int j = 0; j < MERGE_PER; ++j) {
+        for (int j = 0; j < PER; ++j) {
+            const int i = tid + j * SORT_THREADS;
+            nxt[j] = i < qc ? a.skey0[lbase + qb + i] : 0xFFFFFFFFu;
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) other[buf][tid + j * SORT_THREADS] = nxt[j];
+    };
+    int q = seg == 0 ? 1 : 0;
+    if (q < nseg) fetch(q);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
         const int p = tid + j * SORT_THREADS;
         key[j] = p < cnt ? a.skey0[lbase + base0 + p] : 0xFFFFFFFFu;
         rank[j] = (uint32_t)p;
     }
-    for (int q = 0; q < nseg; ++q) {
-        if (q == seg) continue;
-        const int64_t qb = (int64_t)q * SORT_SEG;
-        const int qc = (int)(n - qb < SORT_SEG ? n - qb : SORT_SEG);
-        __syncthreads();
-        for (int i = tid; i < SORT_SEG; i += SORT_THREADS) other[i] = i < qc ? a.skey0[lbase + qb + i] : 0xFFFFFFFFu;
-        __syncthreads();
+    if (q < nseg) stage(0);
+    __syncthreads();
+    int buf = 0;
+    while (q < nseg) {
+        const int q2 = q + 1 == seg ? q + 2 : q + 1;
+        if (q2 < nseg) fetch(q2);
+        const int64_t qb = (int64_t)q * SEG;
+        const int qc = (int)(n - qb < SEG ? n - qb : SEG);
         const uint32_t incl = q < seg ? 1u : 0u;           // equal keys of an earlier segment go first
         // number of i in [0, qc) with other[i] < key + incl (as 64-bit: key may be 0xFFFFFFFF).  The segment is
         // padded to its full power-of-two length with the largest key, so the search has a fixed number of steps
-        // and the MERGE_PER searches of a thread advance together: their LDS reads are in flight at the same time.
-        int lo[MERGE_PER];
+        // and the PER searches of a thread advance together: their LDS reads are in flight at the same time.
+        const uint32_t* oth = other[buf];
+        int lo[PER];
 #pragma unroll
-        for (int j = 0; j < MERGE_PER; ++j) lo[j] = 0;
-        for (int step = SORT_SEG / 2; step >= 1; step >>= 1) {
+        for (int j = 0; j < PER; ++j) lo[j] = 0;
+        for (int step = SEG / 2; step >= 1; step >>= 1) {
 #pragma unroll
-            for (int j = 0; j < MERGE_PER; ++j)
-                if ((uint64_t)other[lo[j] + step - 1] < (uint64_t)key[j] + incl) lo[j] += step;
+            for (int j = 0; j < PER; ++j)
+                if ((uint64_t)oth[lo[j] + step - 1] < (uint64_t)key[j] + incl) lo[j] += step;
         }
 #pragma unroll
-        for (int j = 0; j < MERGE_PER; ++j) {
-            int r = lo[j] + ((uint64_t)other[lo[j]] < (uint64_t)key[j] + incl ? 1 : 0);
+        for (int j = 0; j < PER; ++j) {
+            int r = lo[j] + ((uint64_t)oth[lo[j]] < (uint64_t)key[j] + incl ? 1 : 0);
             rank[j] += (uint32_t)(r < qc ? r : qc);
         }
+        if (q2 < nseg) stage(buf ^ 1);
+        __syncthreads();                                   // this buffer is free again, the other one is filled
+        buf ^= 1;
+        q = q2;
     }
     const float* mx = (list == 0 ? a.smax : a.vmax) + (int64_t)bh * n;
 #pragma unroll
-    for (int j = 0; j < MERGE_PER; ++j) {
+    for (int j = 0; j < PER; ++j) {
         const int p = tid + j * SORT_THREADS;
         if (p < cnt) {
             const int32_t idx = a.sidx0[lbase + base0 + p];
@@ -843,13 +877,28 @@ __global__ void gather_rows_kernel(const unsigned char* src, unsigned char* dst,
         *reinterpret_cast<f32x4*>(d + i) = *reinterpret_cast<const f32x4*>(s + i);
 }
 
-hipError_t run_select(const SelectArgs& a, hipStream_t st) {
-    const int nseg = (int)((a.n + SORT_SEG - 1) / SORT_SEG);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sort_seg_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)SORT_LDS_BYTES);
+template <int SEG>
+static hipError_t launch_sort(const SelectArgs& a, hipStream_t st) {
+    const int nseg = (int)((a.n + SEG - 1) / SEG);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sort_seg_kernel<SEG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sort_lds_bytes(SEG));
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sort_seg_kernel, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), SORT_LDS_BYTES, st, a);
-    hipLaunchKernelGGL(sort_merge_kernel, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), 0, st, a);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sort_merge_kernel<SEG>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 2 * SEG * 4);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sort_seg_kernel<SEG>, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), sort_lds_bytes(SEG), st, a);
+    hipLaunchKernelGGL(sort_merge_kernel<SEG>, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), 2 * SEG * 4, st, a);
+    return hipSuccess;
+}
+
+hipError_t run_select(const SelectArgs& a, hipStream_t st) {
+    // Segment length: the merge's work per workgroup hardly depends on it, the sort's shrinks with it, so the
+    // shortest one that still gives no more workgroups than the chip has compute units (256).
+    const int64_t want = a.n * 2 * a.BH / 256;
+    hipError_t e = want <= SORT_SEG_MIN ? launch_sort<SORT_SEG_MIN>(a, st)
+                 : want <= 4096         ? launch_sort<4096>(a, st)
+                                        : launch_sort<SORT_SEG_MAX>(a, st);
+    if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&walk_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)WALK_LDS_BYTES);
     if (e != hipSuccess) return e;

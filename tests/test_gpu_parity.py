@@ -108,22 +108,24 @@ def test_select_ties_and_capacity(oracle):
     np.testing.assert_array_equal(gpu["accounted"], ref["accounted"])
 
 
-def test_select_ties_across_sort_segments(oracle):
-    """Equal weights spread over several 8192-element sort segments (the last one ragged): the order of
-    equal weights is by index, whichever segment they sit in."""
+@pytest.mark.parametrize("heads", [2, 16, 24])
+def test_select_ties_across_sort_segments(oracle, heads):
+    """Equal weights spread over several sort segments (the last one ragged): the order of equal weights is by
+    index, whichever segment they sit in.  The segment length follows n * heads (2048, 4096 and 8192 here)."""
     n, n_hat = 3 * 8192 + 517, 4000
     rng = np.random.default_rng(11)
-    sc = dict(vert=rng.integers(0, 6, (1, 2, n)).astype(np.float32) / 8192,
-              slash=rng.integers(0, 3, (1, 2, n)).astype(np.float32) / 4096,
-              vmax=np.full((1, 2, n), 2.0 ** -20, np.float32), smax=np.full((1, 2, n), 2.0 ** -21, np.float32))
+    sc = dict(vert=rng.integers(0, 6, (1, heads, n)).astype(np.float32) / 8192,
+              slash=rng.integers(0, 3, (1, heads, n)).astype(np.float32) / 4096,
+              vmax=np.full((1, heads, n), 2.0 ** -20, np.float32), smax=np.full((1, heads, n), 2.0 ** -21, np.float32))
     sc["total"] = sc["vert"].sum(-1).astype(np.float32)
     ref = oracle.select(sc, n_hat, 0.7)
-    q, k, v = inputs.make_plain(1, 2, 1, n, n_hat, 64, dtype="bf16", seed=1)
+    q, k, v = inputs.make_plain(1, heads, 1, n, n_hat, 64, dtype="bf16", seed=1)
     pipe = Pipeline(q, k, v, 8, "bf16")
+    print(f"select ties heads={heads}", flush=True)
     gpu = host(pipe.select(dev_scores(sc), 0.7))
     np.testing.assert_array_equal(gpu["v_cnt"], ref["v_cnt"])
     np.testing.assert_array_equal(gpu["s_cnt"], ref["s_cnt"])
-    for h in range(2):
+    for h in range(heads):
         gv, gs = _sets(gpu, 0, h)
         rv, rs = _sets(ref, 0, h)
         np.testing.assert_array_equal(gv, rv)
