@@ -9,10 +9,10 @@
 //                 output position).  The sorted segments are then merged by rank: every element's
 //                 final position is its position in its segment plus, by bisection, the number of
 //                 elements of the other segments that precede it.
-//   walk_kernel   one workgroup of four waves per head: the greedy loop of Alg. 2 in binary32 with the operands
+//   walk_kernel   one workgroup of six waves per head: the greedy loop of Alg. 2 in binary32 with the operands
 //                 and operation order of the definition.  One wave decides runs of up to 512 picks from one
 //                 list with its lanes, one accumulates the running sum pick by pick behind it and finds
-//                 the pick that reaches the target, and one wave per list stages the sorted list and its
+//                 the pick that reaches the target, and two waves per list stage the sorted list and its
 //                 overlap prefix sums in LDS ahead of both.
 //   emit_kernel   one workgroup per (head, list): the chosen prefix of a sorted list becomes an
 //                 ascending index list (bitmap in LDS + prefix popcount).
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 }
 
 // ---- the greedy loop ----------------------------------------------------------------------------
-// One workgroup of four waves per head.  The loop of Alg. 2 is sequential, but three things about it are not:
+// One workgroup of six waves per head.  The loop of Alg. 2 is sequential, but three things about it are not:
 //   * ol_s after k slashes were taken is the left-to-right binary32 sum of the first k maxima of
 //     the slash list, whatever the interleaving with verticals was (likewise ol_v), so both
 //     running overlaps are prefix arrays that can be filled ahead of the walk (still added one
@@ -247,35 +247,37 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
 // entries and pass the last partial sum to the right neighbour, one lane settling per pass, so every value is
 // the one the sequential loop would hold and each pick sees exactly the operands, operation order and
 // roundings of the definition.
-constexpr int WALK_THREADS = 256;              // wave 0 decides the runs, wave 2 sums, waves 1 and 3 fill the windows of a list each
+constexpr int WALK_THREADS = 384;              // wave 0 decides the runs, wave 2 sums them; per list, waves 1 / 3 stage its
+                                               // weights and lengths and waves 4 / 5 its overlap prefix sums
 constexpr int WALK_E = 8;                      // consecutive list entries a lane looks at: a run has up to 64 * E picks
 constexpr int WALK_RUN = 64 * WALK_E;
-constexpr int WALK_WIN = 3 * WALK_RUN;         // window of a list kept in LDS
-constexpr int WALK_STRIDE = WALK_WIN - WALK_RUN;   // window k of a list covers sorted positions [k * STRIDE, k * STRIDE + WIN)
-static_assert(WALK_E % 2 == 0 && WALK_STRIDE % 128 == 0 && WALK_STRIDE > 0, "walk_scan wants even entry counts per lane");
+constexpr int WALK_BLK = 1024;                 // entries of a list staged at a time
+constexpr int WALK_NBLK = 4;                   // blocks of a list resident in LDS (a ring over sorted positions)
+constexpr int WALK_CAP = WALK_BLK * WALK_NBLK;
+constexpr int WALK_EB = WALK_BLK / 64;         // entries per lane when a block's prefix sums are added
+static_assert(WALK_EB % 2 == 0 && WALK_RUN <= WALK_BLK, "a run never reaches beyond the block after the head's");
 constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the waves (never reached; about a second)
 
-// One window of one sorted list: weights, line lengths, largest entries, and pre[i] = the overlap sum
-// when the first k * STRIDE + i lines of the list have been taken.
-struct WalkWin { float cw[WALK_WIN], cl[WALK_WIN], cm[WALK_WIN], pre[WALK_WIN + 4]; };
+// The resident part of one sorted list, indexed by sorted position modulo WALK_CAP: weights, line lengths, and
+// pre[p] = the overlap sum when the first p lines of the list have been taken.
+struct WalkList { float cw[WALK_CAP], cl[WALK_CAP], pre[WALK_CAP]; };
 // One run of picks from one list: the gain of each pick, how many of them count, and whether the walk ends
 // after them because no line is left that adds anything.
 struct WalkRun { float g[WALK_RUN]; int which, limit, last, pad; };
-struct WalkSync { int ready[2], cur[2], done, err, runs, summed, decided, stop, pad[2]; };
+struct WalkSync { int staged[2], summed_blk[2], cur[2], summed, stop, done, err, runs, decided; float tot[2]; };
+static_assert(offsetof(WalkSync, summed) % 8 == 0 && offsetof(WalkSync, stop) == offsetof(WalkSync, summed) + 4, "summed and stop are read as one 8-byte word");   // tot: a list's whole overlap sum
 constexpr int WALK_RING = 4;                   // runs decided ahead of the running sum
-constexpr size_t WALK_LDS_BYTES = 4 * sizeof(WalkWin) + WALK_RING * sizeof(WalkRun) + sizeof(WalkSync);
+constexpr size_t WALK_LDS_BYTES = 2 * sizeof(WalkList) + WALK_RING * sizeof(WalkRun) + sizeof(WalkSync);
 
 __device__ __forceinline__ int walk_ld(const int* p) { return __builtin_amdgcn_readfirstlane(__atomic_load_n(p, __ATOMIC_RELAXED)); }
 __device__ __forceinline__ void walk_st(int* p, int v) { __atomic_store_n(p, v, __ATOMIC_RELAXED); }
 
-// pre[start + i] = acc + cm[start] + ... + cm[start + i - 1] (added left to right in binary32) for i < 64 * E, by
-// all lanes of a wave; returns the sum behind the last entry.  E is even, start a multiple of 2.
+// Lane j holds the maxima m[0 .. E) of the list entries p0 + E j .. p0 + E j + E - 1.  Writes pre[i] = acc + (the
+// maxima of the entries before entry i of the block, added left to right in binary32) for the 64 E entries of
+// the block, pre pointing at the block's first entry, and returns the sum behind the last entry.  E is even.
 template <int E>
-__device__ __forceinline__ float walk_scan(const float* cm, float* pre, int start, float acc, int lane) {
-    float m[E], x[E];
-    const float2* src = reinterpret_cast<const float2*>(cm + start + E * lane);
-#pragma unroll
-    for (int e = 0; e < E; e += 2) { const float2 t = src[e / 2]; m[e] = t.x; m[e + 1] = t.y; }
+__device__ __forceinline__ float walk_scan(const float (&m)[E], float* pre, float acc, int lane) {
+    float x[E];
     // lane 0 has no left neighbour: the shift hands it 0, and its first addend is acc + m[0], so it holds exactly that
     const float addend0 = lane == 0 ? __fadd_rn(acc, m[0]) : m[0];
 #pragma unroll
@@ -292,11 +294,22 @@ __device__ __forceinline__ float walk_scan(const float* cm, float* pre, int star
     }
     const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
         0, __builtin_bit_cast(int, x[E - 1]), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
-    float2* dst = reinterpret_cast<float2*>(pre + start + E * lane);
+    float2* dst = reinterpret_cast<float2*>(pre + E * lane);
     dst[0] = make_float2(lane == 0 ? acc : left, x[0]);
 #pragma unroll
     for (int e = 2; e < E; e += 2) dst[e / 2] = make_float2(x[e - 1], x[e]);
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[E - 1]), 63));
+}
+
+// m[e] = the largest entry of the line at sorted position pos + e (0 past the end of the list)
+template <int E>
+__device__ __forceinline__ void walk_maxima(const float* m_l, int pos, int n, float (&m)[E]) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int i = pos + e;
+        const float t = m_l[i < n ? i : n - 1];
+        m[e] = i < n ? t : 0.f;
+    }
 }
 
 // Position of the first set bit in the order entry 0 of lane 0, entry 1 of lane 0, ..., entry 0 of lane 1, ...
@@ -313,96 +326,113 @@ __device__ __forceinline__ int walk_first(const uint64_t (&m)[WALK_E]) {
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
 //
-// The waves share only LDS.  Waves 1 and 3 keep two consecutive windows of their list resident (window k goes
-// to buffer k & 1): window k of list l is produced as soon as the deciding wave's current window of that list
-// is >= k - 1, then ready[l] = k + 1 is published; the global loads of the window after it are issued before
-// its sums are added.  The deciding wave (0) publishes cur[l] when it moves on to the next window, which frees
-// the buffer of the one before, and runs = the number of runs it has put into the ring; the summing wave (2)
-// publishes summed = the number of runs it has taken out, and stop when the walk is over.  The summing wave
-// writes the result; the deciding wave ends the producers through `done`.  Every wait is a bounded spin that
-// also ends when another wave has reported a failed wait, so all four waves leave in every case.
+// The waves share only LDS.  Each list is staged in blocks of WALK_BLK sorted positions into a ring of WALK_NBLK
+// blocks: waves 1 / 3 write the weights and line lengths of a block (staged[l] = blocks written), waves 4 / 5
+// its overlap prefix sums, reading the maxima straight from global memory (summed_blk[l]); both load the next
+// block while they work on the current one.  Block b may be written once the deciding wave's head of that list
+// has reached block b - WALK_NBLK + 1 (cur[l] = the head's block): nothing before the head is read again.  The
+// deciding wave (0) needs the head's block and the one after it; it publishes cur[l] and runs = the number of
+// runs it has put into the ring of runs; the summing wave (2) publishes summed = the number of runs it has
+// taken out, and stop when the walk is over.  The summing wave writes the result; the deciding wave ends the
+// stagers through `done`.  Every wait is a bounded spin that also ends when another wave has reported a failed
+// wait, so all six waves leave in every case.
 __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     extern __shared__ __align__(16) unsigned char walk_lds[];
-    WalkWin (*win)[2] = reinterpret_cast<WalkWin (*)[2]>(walk_lds);          // [list][buffer]
-    WalkRun* ring = reinterpret_cast<WalkRun*>(walk_lds + 4 * sizeof(WalkWin));
-    WalkSync* sync = reinterpret_cast<WalkSync*>(walk_lds + 4 * sizeof(WalkWin) + WALK_RING * sizeof(WalkRun));
+    WalkList* lists = reinterpret_cast<WalkList*>(walk_lds);
+    WalkRun* ring = reinterpret_cast<WalkRun*>(walk_lds + 2 * sizeof(WalkList));
+    WalkSync* sync = reinterpret_cast<WalkSync*>(walk_lds + 2 * sizeof(WalkList) + WALK_RING * sizeof(WalkRun));
     const int bh = blockIdx.x, lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = (int)a.n;
+    const int nblk = (n + WALK_BLK - 1) / WALK_BLK;
     const int64_t nh = a.n_hat;
     const int64_t seg_s = ((int64_t)0 * a.BH + bh) * a.n, seg_v = ((int64_t)1 * a.BH + bh) * a.n;
 
     if (threadIdx.x == 0) {
-        sync->ready[0] = sync->ready[1] = 0; sync->cur[0] = sync->cur[1] = 0; sync->done = 0; sync->err = 0;
+        sync->staged[0] = sync->staged[1] = 0; sync->summed_blk[0] = sync->summed_blk[1] = 0;
+        sync->cur[0] = sync->cur[1] = 0; sync->done = 0; sync->err = 0;
         sync->runs = 0; sync->summed = 0; sync->decided = 0; sync->stop = 0;
     }
     __syncthreads();
 
     if (wv == 1 || wv == 3) {
-        // ------------------------------------------------------------------ window producer of one list
+        // ------------------------------------------------------------------ weights and lengths of one list
         const int l = wv == 1 ? 0 : 1;
+        WalkList& L = lists[l];
         const int64_t seg = l == 0 ? seg_s : seg_v;
         const float* w_l = a.sorted_w + seg;
-        const float* m_l = a.sorted_m + seg;
         const int32_t* i_l = a.sidx1 + seg;
         const int nh32 = (int)nh;
-        constexpr int PER = WALK_WIN / 64;
-        float fw[PER], fm[PER]; int32_t fx[PER];           // the window after the last one written to LDS
-        auto fetch = [&](int k) {
-            const int base = k * WALK_STRIDE;
+        constexpr int PER = WALK_BLK / 64;
+        float fw[PER]; int32_t fx[PER];                    // the block after the last one written to LDS
+        auto fetch = [&](int b) {
 #pragma unroll
             for (int j = 0; j < PER; ++j) {
-                const int gi = base + lane + j * 64;
+                const int gi = b * WALK_BLK + lane + j * 64;
                 const int gc = gi < n ? gi : n - 1;
-                fx[j] = i_l[gc]; fw[j] = w_l[gc]; fm[j] = m_l[gc];
+                fx[j] = i_l[gc]; fw[j] = w_l[gc];
             }
         };
         fetch(0);
-        float acc = 0.f;                       // overlap sum behind the last entry scanned so far
-        int produced = 0;
+        int b = 0;
         int spins = 0;
-        while (walk_ld(&sync->done) == 0) {
-            const bool need = produced < walk_ld(&sync->cur[l]) + 2 && (int64_t)produced * WALK_STRIDE < n;
-            if (!need) {
+        while (walk_ld(&sync->done) == 0 && b < nblk) {
+            if (b > walk_ld(&sync->cur[l]) + WALK_NBLK - 1) {
                 __builtin_amdgcn_s_sleep(2);
                 if (++spins > WALK_SPIN_LIMIT) { walk_st(&sync->err, 1); break; }
                 continue;
             }
             spins = 0;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            WalkWin& W = win[l][produced & 1];
-            const WalkWin& P = win[l][(produced & 1) ^ 1];     // the window before this one (still resident)
-            const int base = produced * WALK_STRIDE;
+            const int slot = (b & (WALK_NBLK - 1)) * WALK_BLK;
 #pragma unroll
             for (int j = 0; j < PER; ++j) {
                 const int i = lane + j * 64;
-                const bool in = base + i < n;
+                const bool in = b * WALK_BLK + i < n;
                 const int len = n - fx[j] < nh32 ? n - fx[j] : nh32;       // line length in the n_hat x n block
-                W.cw[i] = in ? fw[j] : 0.f;
-                W.cm[i] = in ? fm[j] : 0.f;
-                W.cl[i] = in ? (float)len : 1.f;
+                L.cw[slot + i] = in ? fw[j] : 0.f;
+                L.cl[slot + i] = in ? (float)len : 1.f;
             }
-            // the first WIN - STRIDE entries are the last ones of the window before: their overlap sums are known
-            if (produced > 0) {
-#pragma unroll
-                for (int j = 0; j < (WALK_WIN - WALK_STRIDE) / 64; ++j)
-                    W.pre[lane + j * 64] = P.pre[WALK_STRIDE + lane + j * 64];
-            }
-            fetch(produced + 1);               // in flight while the sums below are added
+            fetch(b + 1);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
+            ++b;
+            if (lane == 0) walk_st(&sync->staged[l], b);
+        }
+        return;
+    }
+
+    if (wv == 4 || wv == 5) {
+        // ------------------------------------------------------------------ overlap prefix sums of one list
+        // One add after the other, in list order.  Lane j owns E consecutive entries; a pass is "take the last sum
+        // of the lane to the left, add my E maxima one after the other", and pass p settles lane p, so 64 passes
+        // leave every lane with the sums the sequential loop would hold (the lanes to the right of the settled
+        // ones compute values that the later passes replace).
+        const int l = wv - 4;
+        WalkList& L = lists[l];
+        const float* m_l = a.sorted_m + (l == 0 ? seg_s : seg_v);
+        float m[WALK_EB], mn[WALK_EB];
+        walk_maxima<WALK_EB>(m_l, WALK_EB * lane, n, m);
+        float acc = 0.f;                       // overlap sum behind the last entry summed so far
+        int b = 0;
+        int spins = 0;
+        while (walk_ld(&sync->done) == 0 && b < nblk) {
+            if (b > walk_ld(&sync->cur[l]) + WALK_NBLK - 1) {
+                __builtin_amdgcn_s_sleep(2);
+                if (++spins > WALK_SPIN_LIMIT) { walk_st(&sync->err, 1); break; }
+                continue;
+            }
+            spins = 0;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            // The overlap sums of the new entries: one add after the other, in list order.  Lane j owns E consecutive
-            // entries; a pass is "take the last sum of the lane to the left, add my E maxima one after the other",
-            // and pass p settles lane p, so 64 passes leave every lane with the sums the sequential loop would
-            // hold (the lanes to the right of the settled ones compute values that the later passes replace).
-            if (produced == 0) acc = walk_scan<WALK_E>(W.cm, W.pre, 0, acc, lane);
-            acc = walk_scan<(WALK_STRIDE / 64)>(W.cm, W.pre, WALK_WIN - WALK_STRIDE, acc, lane);
-            if (lane == 0) W.pre[WALK_WIN] = acc;
+            walk_maxima<WALK_EB>(m_l, (b + 1) * WALK_BLK + WALK_EB * lane, n, mn);
+            acc = walk_scan<WALK_EB>(m, L.pre + (b & (WALK_NBLK - 1)) * WALK_BLK, acc, lane);
+#pragma unroll
+            for (int e = 0; e < WALK_EB; ++e) m[e] = mn[e];
+            if (b == nblk - 1 && lane == 0) sync->tot[l] = acc;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
-            ++produced;
-            if (lane == 0) walk_st(&sync->ready[l], produced);
+            ++b;
+            if (lane == 0) walk_st(&sync->summed_blk[l], b);
         }
         return;
     }
@@ -450,9 +480,9 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             const float addend0 = lane == 0 ? __fadd_rn(sum, g[0]) : g[0];
 #pragma unroll
             for (int e = 0; e < WALK_E; ++e) x[e] = 0.f;
-            for (int p0 = 0; p0 < limit; p0 += 2 * WALK_E) {
+            for (int p0 = 0; p0 < limit; p0 += 4 * WALK_E) {
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < 4; ++u) {
                     const float left = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
                         0, __builtin_bit_cast(int, x[WALK_E - 1]), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
                     x[0] = __fadd_rn(left, addend0);
@@ -499,63 +529,78 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     // ---------------------------------------------------------------------- the decisions (wave 0)
     const bool early = a.accounted == nullptr;
     int is = 0, iv = 0;                        // heads of the two lists (plain scalars: an array indexed by the
-    int cur_s = 0, cur_v = 0;                  // list would be kept in scratch memory); window each head is in
+    int blk_s = 0, blk_v = 0;                  // list would be kept in scratch memory); block each head is in
+    int have_s = 0, have_v = 0;                // blocks of each list known to be resident (staged and summed)
     int published = 0;                         // runs handed to the summing wave
     bool failed = false;
 
-    auto wait_ready = [&](int l, int k) {      // until window k of list l is resident
-        int spins = 0;
-        while (walk_ld(&sync->ready[l]) <= k) {
+    // until the head's block and the one after it (the first `want` blocks of list l) are resident
+    auto wait_blocks = [&](int l, int want) {
+        int spins = 0, have;
+        for (;;) {
+            const int st = walk_ld(&sync->staged[l]), su = walk_ld(&sync->summed_blk[l]);
+            have = st < su ? st : su;
+            if (have >= want) break;
             __builtin_amdgcn_s_sleep(1);
             if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        return have;
     };
-    wait_ready(0, 0);
-    wait_ready(1, 0);
 
     // What the lanes need of a list when its head is at `h`: lane l looks at the entries h + E l .. h + E l + E - 1
     // (weight, overlap prefix, length), every lane at the head's own three values.  Re-read only when the head of
-    // that list moves.  (A window holds WALK_WIN entries from a start that is at most WALK_STRIDE - 1 before
-    // the head: the 64 E entries after the head are always inside it.)
+    // that list moves.  (All of them lie in the head's block or the one after it.)
     struct View { float cw[WALK_E], pre[WALK_E], cl[WALK_E], w0, l0, ol0; bool ok[WALK_E], has; };
-    auto view = [&](int l, int h, int cw) {
-        const WalkWin& W = win[l][cw & 1];
-        const int base = cw * WALK_STRIDE;
+    auto view = [&](int l, int h) {
+        const WalkList& L = lists[l];
         View r;
 #pragma unroll
         for (int e = 0; e < WALK_E; ++e) {
             const int i = h + WALK_E * lane + e;
-            r.ok[e] = i < n && (i - base) < WALK_WIN;
-            const int ii = r.ok[e] ? i - base : 0;
-            r.cw[e] = W.cw[ii]; r.pre[e] = W.pre[ii]; r.cl[e] = W.cl[ii];
+            r.ok[e] = i < n;
+            const int ii = (i < n ? i : n - 1) & (WALK_CAP - 1);           // nothing is read from a block that never comes
+            r.cw[e] = L.cw[ii]; r.pre[e] = L.pre[ii]; r.cl[e] = L.cl[ii];
         }
         r.has = h < n;
-        const int hh = r.has ? h - base : 0;
-        r.w0 = r.has ? W.cw[hh] : 0.f;                     // an exhausted list: no weight, and its overlap sum
-        r.l0 = r.has ? W.cl[hh] : 1.f;                     // sits right behind its last line
-        r.ol0 = W.pre[h - base];
+        const int hh = (r.has ? h : n - 1) & (WALK_CAP - 1);
+        r.w0 = r.has ? L.cw[hh] : 0.f;                     // an exhausted list: no weight, and its overlap sum
+        r.l0 = r.has ? L.cl[hh] : 1.f;                     // sits right behind its last line
+        r.ol0 = r.has ? L.pre[hh] : sync->tot[l];
         return r;
     };
-    View S = view(0, 0, 0), V = view(1, 0, 0);
+    // blocks a view at head h reads: through the block of entry h + RUN - 1, and pre[h] itself
+    auto blocks_for = [&](int h) {
+        const int want = (h + WALK_RUN - 1) / WALK_BLK + 1;
+        return want < nblk ? want : nblk;
+    };
+    have_s = wait_blocks(0, blocks_for(0));
+    have_v = wait_blocks(1, blocks_for(0));
+    View S = view(0, 0), V = view(1, 0);
+
     while (!failed) {
-        if ((is >= n && iv >= n) || walk_ld(&sync->stop)) break;
-        // move on to the next window of a list once its head has reached that window's start
-        if (is < n && is >= (cur_s + 1) * WALK_STRIDE) {
-            ++cur_s;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the window left behind
-            if (lane == 0) walk_st(&sync->cur[0], cur_s);
-            wait_ready(0, cur_s);
-            if (failed) break;
-            S = view(0, is, cur_s);
+        if (is >= n && iv >= n) break;
+        // a head that has entered a new block frees the blocks behind it; a view that reaches into a block not
+        // known to be resident yet is read again once that block is
+        if (is / WALK_BLK != blk_s && is < n) {
+            blk_s = is / WALK_BLK;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the blocks left behind
+            if (lane == 0) walk_st(&sync->cur[0], blk_s);
         }
-        if (iv < n && iv >= (cur_v + 1) * WALK_STRIDE) {
-            ++cur_v;
+        if (iv / WALK_BLK != blk_v && iv < n) {
+            blk_v = iv / WALK_BLK;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            if (lane == 0) walk_st(&sync->cur[1], cur_v);
-            wait_ready(1, cur_v);
+            if (lane == 0) walk_st(&sync->cur[1], blk_v);
+        }
+        if (is < n && have_s < blocks_for(is)) {
+            have_s = wait_blocks(0, blocks_for(is));
             if (failed) break;
-            V = view(1, iv, cur_v);
+            S = view(0, is);
+        }
+        if (iv < n && have_v < blocks_for(iv)) {
+            have_v = wait_blocks(1, blocks_for(iv));
+            if (failed) break;
+            V = view(1, iv);
         }
         const bool s_has = S.has, v_has = V.has;
         // entry e of lane j: the decision if the walk has taken E j + e more slashes (iv frozen)
@@ -595,12 +640,15 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         int stop_dead = WALK_RUN;
         if (early) stop_dead = walk_first(dead);
         const int limit = run < stop_dead ? run : stop_dead;
-        const View nxt = view(which, (which == 0 ? is : iv) + limit, which == 0 ? cur_s : cur_v);
+        // the list's view after the run (read again above if it reaches into a block that is not resident yet)
+        const View nxt = view(which, (which == 0 ? is : iv) + limit);
         // hand the run over: a free slot of the ring, the gains, then the count of published runs
         bool stopped = false;
         int spins = 0;
-        while (published - walk_ld(&sync->summed) >= WALK_RING) {
-            if (walk_ld(&sync->stop)) { stopped = true; break; }
+        for (;;) {                             // one read: runs taken out of the ring, and whether the walk is over
+            const unsigned long long ss = __atomic_load_n(static_cast<const unsigned long long*>(__builtin_assume_aligned(&sync->summed, 8)), __ATOMIC_RELAXED);
+            if (__builtin_amdgcn_readfirstlane((int)(ss >> 32))) { stopped = true; break; }
+            if (published - __builtin_amdgcn_readfirstlane((int)ss) < WALK_RING) break;
             __builtin_amdgcn_s_sleep(1);
             if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
         }
