@@ -65,16 +65,19 @@ def _sets(sel, b, h):
     return sel["v_idx"][b, h, :nv], sel["s_idx"][b, h, :ns]
 
 
-@pytest.mark.parametrize("alpha", [0.0, 0.5, 0.9, 0.95, 1.0])
-def test_select_bit_exact_on_oracle_scores(oracle, alpha):
-    """Fed the oracle's line weights, the device walk must reproduce the oracle's sets and sum exactly."""
-    cfg = inputs.scaled(inputs.CONFIGS["llama8b_8k"], n=3000, Hq=8, Hkv=2, heavy_lo=16, heavy_hi=48, span=128)
+@pytest.mark.parametrize("alpha,n", [(0.0, 3000), (0.5, 3000), (0.9, 3000), (0.95, 3000), (1.0, 3000),
+                                     (0.95, 2048), (1.0, 2048), (1.0, 5120)])
+def test_select_bit_exact_on_oracle_scores(oracle, alpha, n):
+    """Fed the oracle's line weights, the device walk must reproduce the oracle's sets and sum exactly.
+    (Lengths that are multiples of 1024 end a list exactly at the end of a staged block; alpha = 1 walks both
+    lists to their ends.)"""
+    cfg = inputs.scaled(inputs.CONFIGS["llama8b_8k"], n=n, Hq=8, Hkv=2, heavy_lo=16, heavy_hi=48, span=128)
     q, k, v, _ = inputs.make_inputs(cfg)
     sc = oracle.score(q[:, :, -cfg.w:], k)
     ref = oracle.select(sc, cfg.n_hat, alpha)
     pipe = Pipeline(q, k, v, cfg.w, cfg.dtype)
     for with_acc in (True, False):
-        print(f"select alpha={alpha} accounted={with_acc}", flush=True)
+        print(f"select alpha={alpha} n={n} accounted={with_acc}", flush=True)
         gpu = host(pipe.select(dev_scores(sc), alpha, accounted=with_acc))
         np.testing.assert_array_equal(gpu["v_cnt"], ref["v_cnt"])
         np.testing.assert_array_equal(gpu["s_cnt"], ref["s_cnt"])
