@@ -252,13 +252,9 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     if (c->profile) {
         if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
             return fail(c, LS_EHIP, "ls_sparse_prefill: hipEventCreate failed");
-        (void)hipEventRecord(e0, static_cast<hipStream_t>(stream));
     }
-    e = ls::launch_prefill(a, s->dtype, s->d, static_cast<hipStream_t>(stream));
-    if (c->profile) {
-        (void)hipEventRecord(e1, static_cast<hipStream_t>(stream));
-        c->events.emplace_back(e0, e1);
-    }
+    e = ls::launch_prefill(a, s->dtype, s->d, static_cast<hipStream_t>(stream), e0, e1);
+    if (c->profile) c->events.emplace_back(e0, e1);
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: %s", hipGetErrorString(e));
     return LS_OK;
 }

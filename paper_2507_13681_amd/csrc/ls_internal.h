@@ -111,7 +111,8 @@ hipError_t run_gather_rows(const void* src, void* dst, const int32_t* keep_idx, 
                            int BK, int64_t len, int budget, int row_bytes, hipStream_t st);
 hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st);
 hipError_t launch_sched(const SchedArgs& a, hipStream_t st);
-hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st);
+// ev0 / ev1 (both or neither): events that receive the start and stop time of the attention kernel's own dispatch
+hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len);
 int prefill_block_rows();
 

@@ -22,6 +22,7 @@
 // Tile products: S^T = K_tile * Q^T and O^T += V_tile^T * P^T on 32x32 MFMA, fp32 accumulation,
 // online softmax in the base-2 domain.  K is staged row-major in LDS, V transposed (see vt_col).
 #include <type_traits>
+#include <hip/hip_ext.h>
 #include "ls_device.h"
 #include "ls_internal.h"
 
@@ -1065,17 +1066,19 @@ static bool prefill_bf16_oblds(int words, int tab_len) {
 }
 
 template <int D, bool OBLDS>
-static hipError_t launch_prefill_bf16_t(const PrefillArgs& a, hipStream_t st) {
+static hipError_t launch_prefill_bf16_t(const PrefillArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     const size_t smem = prefill_bf16_smem<D>(a.words, a.tab_len, OBLDS);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_bf16_kernel<D, OBLDS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_bf16_kernel<D, OBLDS>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
+    // with events: they take the start and stop time stamps of this dispatch itself, no marker goes into the stream
+    if (ev0 && ev1) hipExtLaunchKernelGGL((prefill_bf16_kernel<D, OBLDS>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), (uint32_t)smem, st, ev0, ev1, 0, a);
+    else hipLaunchKernelGGL((prefill_bf16_kernel<D, OBLDS>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
     return hipGetLastError();
 }
 template <int D>
-static hipError_t launch_prefill_bf16(const PrefillArgs& a, hipStream_t st) {
-    return prefill_bf16_oblds<D>(a.words, a.tab_len) ? launch_prefill_bf16_t<D, true>(a, st) : launch_prefill_bf16_t<D, false>(a, st);
+static hipError_t launch_prefill_bf16(const PrefillArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+    return prefill_bf16_oblds<D>(a.words, a.tab_len) ? launch_prefill_bf16_t<D, true>(a, st, ev0, ev1) : launch_prefill_bf16_t<D, false>(a, st, ev0, ev1);
 }
 
 template <typename T, int D>
@@ -1086,12 +1089,13 @@ static size_t prefill_smem_t(int words, int tab_len) {
 }
 
 template <typename T, int D>
-static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st) {
+static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     const size_t smem = prefill_smem_t<T, D>(a.words, a.tab_len);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<T, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_kernel<T, D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
+    if (ev0 && ev1) hipExtLaunchKernelGGL((prefill_kernel<T, D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), (uint32_t)smem, st, ev0, ev1, 0, a);
+    else hipLaunchKernelGGL((prefill_kernel<T, D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
     return hipGetLastError();
 }
 
@@ -1118,11 +1122,11 @@ hipError_t launch_sched(const SchedArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st) {
-    if (dtype == 0 && d == 128) return launch_prefill_bf16<128>(a, st);
-    if (dtype == 0 && d == 64) return launch_prefill_bf16<64>(a, st);
-    if (dtype == 1 && d == 128) return launch_prefill_t<float, 128>(a, st);
-    if (dtype == 1 && d == 64) return launch_prefill_t<float, 64>(a, st);
+hipError_t launch_prefill(const PrefillArgs& a, int dtype, int d, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+    if (dtype == 0 && d == 128) return launch_prefill_bf16<128>(a, st, ev0, ev1);
+    if (dtype == 0 && d == 64) return launch_prefill_bf16<64>(a, st, ev0, ev1);
+    if (dtype == 1 && d == 128) return launch_prefill_t<float, 128>(a, st, ev0, ev1);
+    if (dtype == 1 && d == 64) return launch_prefill_t<float, 64>(a, st, ev0, ev1);
     return hipErrorInvalidValue;
 }
 
