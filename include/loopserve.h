@@ -173,9 +173,10 @@ size_t ls_decode_workspace_bytes(const ls_shape* shape, int32_t cap, int32_t T);
 
 /*
  * Timing of the sparse attention kernel itself (the dominant kernel of ls_sparse_prefill), for
- * roofline reports.  After ls_profile_enable(ctx, 1) every ls_sparse_prefill call brackets that
- * one kernel launch with HIP events on the call's stream (this creates two events per call, so
- * leave it off in allocation-free loops).  ls_profile_prefill_kernel_ms waits for the recorded
+ * roofline reports.  After ls_profile_enable(ctx, 1) every ls_sparse_prefill call attaches a pair
+ * of HIP events to that one kernel launch on the call's stream: they receive the start and stop
+ * time of the dispatch itself, and no marker is put into the stream (this creates two events per
+ * call, so leave it off in allocation-free loops).  ls_profile_prefill_kernel_ms waits for the recorded
  * events and returns the mean kernel duration in milliseconds and the number of launches seen since
  * profiling was enabled.  ls_profile_enable(ctx, 0) stops recording and drops the events.
  */
