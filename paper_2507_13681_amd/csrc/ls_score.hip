@@ -318,15 +318,21 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
                 float ssum = 0.f, smx = 0.f;
                 const int t0 = j - (SB - 1) > 0 ? j - (SB - 1) : 0;
                 const int t1 = j < a.w - 1 ? j : a.w - 1;
-                // rows in ascending order, eight reads in flight; a row outside t0..t1 adds an exact zero
+                // rows in ascending order, eight reads in flight; whole groups of eight need no range tests, the
+                // last, shorter group adds an exact zero for a row beyond t1
                 const float* dp = slab + (SB - 1) - j;             // row t of this diagonal sits at dp[t * (SB + 2)]
-                for (int tb = t0 & ~7; tb <= t1; tb += 8) {
+                int tb = t0;
+                for (; tb + 7 <= t1; tb += 8) {
                     float p8[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int t = tb + e;
-                        p8[e] = (t >= t0 && t <= t1) ? dp[t * (SB + 2)] : 0.f;
-                    }
+                    for (int e = 0; e < 8; ++e) p8[e] = dp[(tb + e) * (SB + 2)];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) { ssum += p8[e]; smx = fmaxf(smx, p8[e]); }
+                }
+                if (tb <= t1) {
+                    float p8[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p8[e] = (tb + e <= t1) ? dp[(tb + e) * (SB + 2)] : 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) { ssum += p8[e]; smx = fmaxf(smx, p8[e]); }
                 }
