@@ -77,7 +77,27 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
         uint16_t* iout = (pass & 1) ? ib0 : ib1;
         for (int i = tid; i < SORT_WAVES * 256; i += SORT_THREADS) (&hist[0][0])[i] = 0u;
         __syncthreads();
-        for (int i = lo + lane; i < lo + SLICE; i += 64) atomicAdd(&hist[wv][(kin[i] >> shift) & 255u], 1u);
+        if (pass < 3) {
+            for (int i = lo + lane; i < lo + SLICE; i += 64) atomicAdd(&hist[wv][(kin[i] >> shift) & 255u], 1u);
+        } else {
+            // the top byte (sign and upper exponent bits) takes few values, and 64 atomics on one counter take turns:
+            // three times over, the lanes that share the digit of the first lane not yet counted add once together;
+            // what is left adds one by one
+            for (int i = lo + lane; i < lo + SLICE; i += 64) {
+                const uint32_t dg = kin[i] >> 24;
+                uint64_t todo = ~0ull;
+#pragma unroll
+                for (int round = 0; round < 3; ++round) {
+                    if (todo == 0ull) break;
+                    const int first = __ffsll((unsigned long long)todo) - 1;
+                    const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)dg, first);
+                    const uint64_t same = __ballot(dg == d0) & todo;
+                    if (lane == first) atomicAdd(&hist[wv][d0], (uint32_t)__popcll(same));
+                    todo &= ~same;
+                }
+                if ((todo >> lane) & 1ull) atomicAdd(&hist[wv][dg], 1u);
+            }
+        }
         __syncthreads();
         // exclusive offsets in (digit, wave) order
         if (tid < 256) {
