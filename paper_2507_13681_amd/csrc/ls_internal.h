@@ -20,6 +20,8 @@ struct ScoreArgs {
     float* gscore;            // [B*Hkv][n]       group-summed column sums (retention score)
 };
 
+constexpr int SELECT_HEAD_LINES = 1024;   // lines at the front of each sorted list whose weight and maximum are stored in order
+
 struct SelectArgs {
     int64_t n, n_hat;
     int BH;
@@ -27,7 +29,7 @@ struct SelectArgs {
     const float *vert, *slash, *vmax, *smax, *total;
     uint32_t *skey0, *skey1;  // [2][BH][n] sorted keys of each 8192-element segment (skey0; skey1 is spare)
     int32_t *sidx0, *sidx1;   // [2][BH][n] line indices per sorted segment (sidx0) and of the merged order (sidx1)
-    float *sorted_w, *sorted_m;   // [2][BH][n]
+    float *head_w, *head_m;   // [2][BH][SELECT_HEAD_LINES] weight and largest entry of the first lines of each sorted list
     int32_t *v_idx, *v_cnt, *s_idx, *s_cnt;
     int cap_v, cap_s;
     float* accounted;         // may be null

@@ -36,6 +36,8 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {
     return __builtin_bit_cast(float, u);
 }
 
+constexpr int WALK_BLK = 1024;                 // entries of a sorted list the walk stages at a time
+static_assert(WALK_BLK == SELECT_HEAD_LINES, "the merge writes the walk's first block in order");
 constexpr int SORT_THREADS = 1024;
 constexpr int SORT_WAVES = 16;
 constexpr int SORT_SEG_MAX = 8192;             // most elements one workgroup sorts inside LDS
@@ -169,7 +171,9 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
 // number of elements of every other segment that go before it: smaller key, or equal key in a segment
 // of smaller line indices (the order stays stable).  The other segments' sorted keys are staged in
 // LDS one at a time (two buffers: the next segment is loaded while the current one is searched) and
-// searched by bisection.  Writes the sorted weights, line indices (sidx1) and each line's largest entry.
+// searched by bisection.  Writes the line indices in sorted order (sidx1): a scattered store per line, which is
+// why the weights and maxima are not written beside them; the walk fetches those through the indices, and only
+// for the part of the order it gets to.
 // Dynamic LDS: 2 * SEG keys.
 template <int SEG>
 __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) {
@@ -236,15 +240,18 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
         buf ^= 1;
         q = q2;
     }
+    // (the first WALK_BLK lines of the order also get their weight and maximum written, so that the walk can start
+    // without a second round trip through the indices)
     const float* mx = (list == 0 ? a.smax : a.vmax) + (int64_t)bh * n;
+    float* hw = a.head_w + ((int64_t)list * a.BH + bh) * WALK_BLK;
+    float* hm = a.head_m + ((int64_t)list * a.BH + bh) * WALK_BLK;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
         const int p = tid + j * SORT_THREADS;
         if (p < cnt) {
             const int32_t idx = a.sidx0[lbase + base0 + p];
-            a.sorted_w[lbase + rank[j]] = key_to_float(key[j]);
             a.sidx1[lbase + rank[j]] = idx;
-            a.sorted_m[lbase + rank[j]] = mx[idx];
+            if (rank[j] < (uint32_t)WALK_BLK) { hw[rank[j]] = key_to_float(key[j]); hm[rank[j]] = mx[idx]; }
         }
     }
 }
@@ -271,7 +278,6 @@ constexpr int WALK_THREADS = 384;              // wave 0 decides the runs, wave 
                                                // weights and lengths and waves 4 / 5 its overlap prefix sums
 constexpr int WALK_E = 8;                      // consecutive list entries a lane looks at: a run has up to 64 * E picks
 constexpr int WALK_RUN = 64 * WALK_E;
-constexpr int WALK_BLK = 1024;                 // entries of a list staged at a time
 constexpr int WALK_NBLK = 4;                   // blocks of a list resident in LDS (a ring over sorted positions)
 constexpr int WALK_CAP = WALK_BLK * WALK_NBLK;
 constexpr int WALK_EB = WALK_BLK / 64;         // entries per lane when a block's prefix sums are added
@@ -321,14 +327,31 @@ __device__ __forceinline__ float walk_scan(const float (&m)[E], float* pre, floa
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[E - 1]), 63));
 }
 
-// m[e] = the largest entry of the line at sorted position pos + e (0 past the end of the list)
+// ix[e] = the line at sorted position pos + e (the last line's index past the end of the list)
 template <int E>
-__device__ __forceinline__ void walk_maxima(const float* m_l, int pos, int n, float (&m)[E]) {
+__device__ __forceinline__ void walk_indices(const int32_t* i_l, int pos, int n, int32_t (&ix)[E]) {
+    typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+    // (a wave-uniform choice: the list starts on a 16-byte boundary and the wave's last entry is inside it)
+    const bool whole = (reinterpret_cast<uintptr_t>(i_l) & 15) == 0 && (pos & 3) == 0 &&
+                       __builtin_amdgcn_readfirstlane(pos) + 64 * E <= n;
+    if (E % 4 == 0 && whole) {
+#pragma unroll
+        for (int e = 0; e < E; e += 4) {
+            const i32x4 v = *reinterpret_cast<const i32x4*>(i_l + pos + e);
+            ix[e] = v.x; ix[e + 1] = v.y; ix[e + 2] = v.z; ix[e + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) { const int i = pos + e; ix[e] = i_l[i < n ? i : n - 1]; }
+    }
+}
+// m[e] = the largest entry of line ix[e], the line at sorted position pos + e (0 past the end of the list)
+template <int E>
+__device__ __forceinline__ void walk_maxima(const float* m_l, const int32_t (&ix)[E], int pos, int n, float (&m)[E]) {
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        const int i = pos + e;
-        const float t = m_l[i < n ? i : n - 1];
-        m[e] = i < n ? t : 0.f;
+        const float t = m_l[ix[e]];
+        m[e] = pos + e < n ? t : 0.f;
     }
 }
 
@@ -380,20 +403,32 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         const int l = wv == 1 ? 0 : 1;
         WalkList& L = lists[l];
         const int64_t seg = l == 0 ? seg_s : seg_v;
-        const float* w_l = a.sorted_w + seg;
+        const float* w_l = (l == 0 ? a.slash : a.vert) + (int64_t)bh * a.n;   // weights by line index
         const int32_t* i_l = a.sidx1 + seg;
         const int nh32 = (int)nh;
         constexpr int PER = WALK_BLK / 64;
-        float fw[PER]; int32_t fx[PER];                    // the block after the last one written to LDS
-        auto fetch = [&](int b) {
+        // the block after the last one written to LDS (indices and weights), and the indices of the one after it:
+        // the weights are fetched through the indices, so the indices are requested a block earlier
+        float fw[PER]; int32_t fx[PER], fxn[PER];
+        auto fetch_idx = [&](int b, int32_t (&x)[PER]) {
 #pragma unroll
             for (int j = 0; j < PER; ++j) {
                 const int gi = b * WALK_BLK + lane + j * 64;
-                const int gc = gi < n ? gi : n - 1;
-                fx[j] = i_l[gc]; fw[j] = w_l[gc];
+                x[j] = i_l[gi < n ? gi : n - 1];
             }
         };
-        fetch(0);
+        auto fetch = [&](int b) {                          // fx <- fxn (block b), its weights, and block b + 1's indices
+#pragma unroll
+            for (int j = 0; j < PER; ++j) { fx[j] = fxn[j]; fw[j] = w_l[fx[j]]; }
+            fetch_idx(b + 1, fxn);
+        };
+        {                                                  // block 0: its weights were written in order by the merge
+            const float* hw = a.head_w + ((int64_t)l * a.BH + bh) * WALK_BLK;
+            fetch_idx(0, fx);
+#pragma unroll
+            for (int j = 0; j < PER; ++j) { const int gi = lane + j * 64; fw[j] = hw[gi < n ? gi : n - 1]; }
+            fetch_idx(1, fxn);
+        }
         int b = 0;
         int spins = 0;
         while (walk_ld(&sync->done) == 0 && b < nblk) {
@@ -430,9 +465,16 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         // ones compute values that the later passes replace).
         const int l = wv - 4;
         WalkList& L = lists[l];
-        const float* m_l = a.sorted_m + (l == 0 ? seg_s : seg_v);
+        const int32_t* i_l = a.sidx1 + (l == 0 ? seg_s : seg_v);
+        const float* m_l = (l == 0 ? a.smax : a.vmax) + (int64_t)bh * a.n;     // maxima by line index
         float m[WALK_EB], mn[WALK_EB];
-        walk_maxima<WALK_EB>(m_l, WALK_EB * lane, n, m);
+        int32_t ix[WALK_EB];                   // line indices of the block after the next one's maxima
+        {                                      // block 0: its maxima were written in order by the merge
+            const float* hm = a.head_m + ((int64_t)l * a.BH + bh) * WALK_BLK;
+#pragma unroll
+            for (int e = 0; e < WALK_EB; ++e) { const int i = WALK_EB * lane + e; const float t = hm[i < n ? i : n - 1]; m[e] = i < n ? t : 0.f; }
+        }
+        walk_indices<WALK_EB>(i_l, WALK_BLK + WALK_EB * lane, n, ix);
         float acc = 0.f;                       // overlap sum behind the last entry summed so far
         int b = 0;
         int spins = 0;
@@ -444,7 +486,8 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             }
             spins = 0;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            walk_maxima<WALK_EB>(m_l, (b + 1) * WALK_BLK + WALK_EB * lane, n, mn);
+            walk_maxima<WALK_EB>(m_l, ix, (b + 1) * WALK_BLK + WALK_EB * lane, n, mn);
+            walk_indices<WALK_EB>(i_l, (b + 2) * WALK_BLK + WALK_EB * lane, n, ix);
             acc = walk_scan<WALK_EB>(m, L.pre + (b & (WALK_NBLK - 1)) * WALK_BLK, acc, lane);
 #pragma unroll
             for (int e = 0; e < WALK_EB; ++e) m[e] = mn[e];
