@@ -87,7 +87,7 @@ size_t ws_score(const ls_shape* s, bool lines) {
 }
 size_t ws_select(const ls_shape* s) {
     const size_t BH = (size_t)s->B * s->Hq;
-    return 4 * up(2 * BH * (size_t)s->n * 4) + 2 * up(2 * BH * ls::SELECT_HEAD_LINES * 4);
+    return 3 * up(2 * BH * (size_t)s->n * 4) + 2 * up(2 * BH * ls::SELECT_HEAD_LINES * 4);
 }
 inline int words_of(int64_t n) { return (int)((n + 31) / 32) + 8; }
 inline int tab_len_of(int64_t n) { return (int)(n / 64) + 4; }
@@ -186,7 +186,7 @@ int ls_select(ls_ctx* c, const ls_shape* s, float alpha,
     a.vert = vert; a.slash = slash; a.vmax = vmax; a.smax = smax; a.total = total;
     Bump bp{c->ws, c->ws_bytes, 0};
     const size_t cnt = 2 * (size_t)a.BH * (size_t)a.n;
-    a.skey0 = bp.take<uint32_t>(cnt); a.skey1 = bp.take<uint32_t>(cnt);
+    a.skey0 = bp.take<uint32_t>(cnt);
     a.sidx0 = bp.take<int32_t>(cnt); a.sidx1 = bp.take<int32_t>(cnt);
     a.head_w = bp.take<float>(2 * (size_t)a.BH * ls::SELECT_HEAD_LINES); a.head_m = bp.take<float>(2 * (size_t)a.BH * ls::SELECT_HEAD_LINES);
     if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_select: workspace of %zu bytes is too small", c->ws_bytes);

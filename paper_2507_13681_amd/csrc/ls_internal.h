@@ -27,8 +27,8 @@ struct SelectArgs {
     int BH;
     float alpha;
     const float *vert, *slash, *vmax, *smax, *total;
-    uint32_t *skey0, *skey1;  // [2][BH][n] sorted keys of each 8192-element segment (skey0; skey1 is spare)
-    int32_t *sidx0, *sidx1;   // [2][BH][n] line indices per sorted segment (sidx0) and of the merged order (sidx1)
+    uint32_t* skey0;          // [2][BH][n] sorted keys of each segment
+    int32_t *sidx0, *sidx1;   // [2][BH][n] line indices of each sorted segment (sidx0) and of the merged order (sidx1)
     float *head_w, *head_m;   // [2][BH][SELECT_HEAD_LINES] weight and largest entry of the first lines of each sorted list
     int32_t *v_idx, *v_cnt, *s_idx, *s_cnt;
     int cap_v, cap_s;
