@@ -217,24 +217,38 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_merge_kernel(SelectArgs a) 
         if (q2 < nseg) fetch(q2);
         const int64_t qb = (int64_t)q * SEG;
         const int qc = (int)(n - qb < SEG ? n - qb : SEG);
-        const uint32_t incl = q < seg ? 1u : 0u;           // equal keys of an earlier segment go first
-        // number of i in [0, qc) with other[i] < key + incl (as 64-bit: key may be 0xFFFFFFFF).  The segment is
-        // padded to its full power-of-two length with the largest key, so the search has a fixed number of steps
-        // and the PER searches of a thread advance together: their LDS reads are in flight at the same time.
-        const uint32_t* oth = other[buf];
-        int lo[PER];
+        // number of i in [0, qc) with other[i] before key: other[i] < key, or <= key when the other segment is an
+        // earlier one (its equal keys go first).  The segment is padded to its full power-of-two length with the
+        // largest key, so the search has a fixed number of steps and the PER searches of a thread advance together:
+        // their LDS reads are in flight at the same time (plain 32-bit compares: a 64-bit "key + 1" compare made the
+        // compiler funnel all reads through one register pair, one wait each).
+        // (positions are kept as LDS byte addresses: a probe then needs no address arithmetic beyond the
+        // instruction's own offset)
+        typedef const __attribute__((address_space(3))) uint32_t* lds_u32;
+        const uint32_t base = (uint32_t)(uintptr_t)(lds_u32)other[buf];
+        uint32_t la[PER];
 #pragma unroll
-        for (int j = 0; j < PER; ++j) lo[j] = 0;
-        for (int step = SEG / 2; step >= 1; step >>= 1) {
+        for (int j = 0; j < PER; ++j) la[j] = base;
+        auto search = [&](auto earlier) {
+            constexpr bool le = decltype(earlier)::value;
 #pragma unroll
-            for (int j = 0; j < PER; ++j)
-                if ((uint64_t)oth[lo[j] + step - 1] < (uint64_t)key[j] + incl) lo[j] += step;
-        }
+            for (int step = SEG / 2; step >= 1; step >>= 1) {
+                uint32_t o[PER];
 #pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            int r = lo[j] + ((uint64_t)oth[lo[j]] < (uint64_t)key[j] + incl ? 1 : 0);
-            rank[j] += (uint32_t)(r < qc ? r : qc);
-        }
+                for (int j = 0; j < PER; ++j) o[j] = *(lds_u32)(uintptr_t)(la[j] + 4u * (uint32_t)(step - 1));
+#pragma unroll
+                for (int j = 0; j < PER; ++j) if (le ? o[j] <= key[j] : o[j] < key[j]) la[j] += 4u * (uint32_t)step;
+            }
+            uint32_t o[PER];
+#pragma unroll
+            for (int j = 0; j < PER; ++j) o[j] = *(lds_u32)(uintptr_t)la[j];
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const int r = (int)((la[j] - base) >> 2) + ((le ? o[j] <= key[j] : o[j] < key[j]) ? 1 : 0);
+                rank[j] += (uint32_t)(r < qc ? r : qc);
+            }
+        };
+        if (q < seg) search(std::true_type{}); else search(std::false_type{});
         if (q2 < nseg) stage(buf ^ 1);
         __syncthreads();                                   // this buffer is free again, the other one is filled
         buf ^= 1;
