@@ -79,14 +79,20 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
         uint16_t* iout = (pass & 1) ? ib0 : ib1;
         for (int i = tid; i < SORT_WAVES * 256; i += SORT_THREADS) (&hist[0][0])[i] = 0u;
         __syncthreads();
+        // this wave's slice, read once per pass and ahead of the counting (the compiler does not move reads across atomics)
+        uint32_t keys[SLICE / 64]; uint16_t idxs[SLICE / 64];
+#pragma unroll
+        for (int c = 0; c < SLICE / 64; ++c) { keys[c] = kin[lo + 64 * c + lane]; idxs[c] = iin[lo + 64 * c + lane]; }
         if (pass < 3) {
-            for (int i = lo + lane; i < lo + SLICE; i += 64) atomicAdd(&hist[wv][(kin[i] >> shift) & 255u], 1u);
+#pragma unroll
+            for (int c = 0; c < SLICE / 64; ++c) atomicAdd(&hist[wv][(keys[c] >> shift) & 255u], 1u);
         } else {
             // the top byte (sign and upper exponent bits) takes few values, and 64 atomics on one counter take turns:
             // three times over, the lanes that share the digit of the first lane not yet counted add once together;
             // what is left adds one by one
-            for (int i = lo + lane; i < lo + SLICE; i += 64) {
-                const uint32_t dg = kin[i] >> 24;
+#pragma unroll
+            for (int c = 0; c < SLICE / 64; ++c) {
+                const uint32_t dg = keys[c] >> 24;
                 uint64_t todo = ~0ull;
 #pragma unroll
                 for (int round = 0; round < 3; ++round) {
@@ -130,9 +136,6 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_seg_kernel(SelectArgs a) {
         // (the wave's counters are read and written with relaxed atomics: plain LDS accesses that the compiler keeps
         // in program order around the wave barriers; a volatile pointer would turn them into flat accesses)
         uint32_t* myh = hist[wv];
-        uint32_t keys[SLICE / 64]; uint16_t idxs[SLICE / 64];    // the slice is only read during the scatter
-#pragma unroll
-        for (int c = 0; c < SLICE / 64; ++c) { keys[c] = kin[lo + 64 * c + lane]; idxs[c] = iin[lo + 64 * c + lane]; }
 #pragma unroll
         for (int c = 0; c < SLICE / 64; ++c) {
             const uint32_t key = keys[c];
