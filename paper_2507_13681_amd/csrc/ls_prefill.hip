@@ -97,19 +97,20 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             // The list is ascending, so neighbouring lanes mostly hit the same bitmap word: their bits are OR-ed
-            // across each run of equal words first (five doubling steps reach 32 lanes) and the run's first lane,
-            // and every 32nd lane, does the one atomic.  Correct for any order of the list.
+            // across each run of equal words inside a row of 16 lanes first (four doubling steps of row shifts,
+            // plain vector moves) and the run's first lane, and every 16th lane, does the one atomic.  Correct for
+            // any order of the list.
             const bool ok = o8[j] >= 0 && o8[j] < n;
             const int wd = ok ? o8[j] >> 5 : -1 - (tid & 63);
             uint32_t m = ok ? 1u << (o8[j] & 31) : 0u;
-#pragma unroll
-            for (int off = 1; off < 32; off <<= 1) {
-                const uint32_t tm = __shfl_down(m, off, 64);
-                const int tw = __shfl_down(wd, off, 64);
-                if ((tid & 63) + off < 64 && tw == wd) m |= tm;
-            }
-            const int pw = __shfl_up(wd, 1, 64);
-            if (ok && (((tid & 31) == 0) || pw != wd)) atomicOr(&sm[wd], m);
+            // value of the lane `off` to the right inside the row (lanes shifted in from outside a row read -2 / 0)
+#define LS_ROW_SHL(x, off, fill) __builtin_amdgcn_update_dpp((int)(fill), (int)(x), 0x100 + (off), 0xF, 0xF, false)
+#define LS_OR_STEP(off) { const uint32_t tm = (uint32_t)LS_ROW_SHL(m, off, 0); const int tw = LS_ROW_SHL(wd, off, -2); if (tw == wd) m |= tm; }
+            LS_OR_STEP(1) LS_OR_STEP(2) LS_OR_STEP(4) LS_OR_STEP(8)
+            const int pw = __builtin_amdgcn_update_dpp(-2, wd, 0x110 + 1 /* row_shr:1 */, 0xF, 0xF, false);
+#undef LS_OR_STEP
+#undef LS_ROW_SHL
+            if (ok && pw != wd) atomicOr(&sm[wd], m);
         }
     }
     __syncthreads();
@@ -117,7 +118,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     uint32_t* og = a.obits + (int64_t)bh * (words + 1);       // one zero word, then the bitmap
     if (tid == 0) og[0] = 0u;
     for (int i = tid; i < words; i += blockDim.x) { og[i + 1] = sm[i]; mine += __popc(sm[i]); }
-    atomicAdd(&total_bits, mine);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_down(mine, off, 64);       // one atomic per wave, not per thread
+    if ((tid & 63) == 0) atomicAdd(&total_bits, mine);
     // activity table
     for (int e = tid; e < a.tab_len; e += blockDim.x) {
         const int64_t j = (int64_t)e - 1;
