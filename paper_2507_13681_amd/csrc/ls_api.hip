@@ -73,10 +73,10 @@ inline float scale_log2e(const ls_shape* s) {
     return sc * 1.44269504088896340736f;
 }
 
-// per key block max / sum of every scored row; later the 8 partial totals of every head and its arrival counter
+// per key block max / sum of every scored row; later the 8 partial totals of every head
 inline size_t part_floats(const ls_shape* s) {
     const size_t BH = (size_t)s->B * s->Hq;
-    const size_t a = BH * s->w * nkb_of(s->n) * 2, b = BH * 9;
+    const size_t a = BH * s->w * nkb_of(s->n) * 2, b = BH * 8;
     return a > b ? a : b;
 }
 size_t ws_score(const ls_shape* s, bool lines) {

@@ -26,7 +26,6 @@ namespace ls {
 
 constexpr int SB = 128;           // keys per workgroup
 constexpr int SCORE_THREADS = 256;
-constexpr int FINISH_SPLIT = 8;   // workgroups of finish_kernel per head (a head alone is a string of load round trips)
 
 template <typename T, int D>
 __device__ __forceinline__ void load_k_frags(Frag<T> (&kf)[D / 16], const T* Kg, int64_t key, int64_t n, int g) {
@@ -241,9 +240,6 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
         const int64_t rel = p - blk0;                      // key klocal of the block is visible to row i iff klocal <= rel
         ql[i] = rel < -1 ? -1 : (rel > SB ? SB : (int32_t)rel);
     }
-    // the arrival counters of finish_kernel (behind its partial totals; `part` is free since merge_kernel has run)
-    if (MODE != 2 && kb == 0 && bk == 0)
-        for (int i = tid; i < a.BH; i += SCORE_THREADS) reinterpret_cast<uint32_t*>(a.part)[(int64_t)a.BH * FINISH_SPLIT + i] = 0u;
     // every key of the block is visible to every row of a contiguous window (all but the last blocks)
     const bool open = a.q_pos == nullptr && blk0 + SB - 1 <= n - a.w;
     const int rgs = wpad / 32;
@@ -351,6 +347,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
 // ---- finish: add the two diagonal partials, reduce the total ------------------------------------
 // grid (B*Hq).  Diagonal o is met by keys n-w-o .. n-1-o (clipped at 0), i.e. by key blocks
 // kA = max(0, n-w-o)/SB and kB = (n-1-o)/SB, which are equal or adjacent.
+constexpr int FINISH_SPLIT = 8;            // workgroups per head (a head alone is a string of load round trips)
 __global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguous) {
     __shared__ float red[1024];
     const int bh = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
@@ -395,21 +392,15 @@ __global__ __launch_bounds__(1024) void finish_kernel(ScoreArgs a, int contiguou
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    // the workgroup of a head that arrives last adds the ranges' shares, in a fixed tree order whoever it is
-    if (tid == 0) {
-        float* p = a.part + (int64_t)bh * FINISH_SPLIT;
-        p[part] = red[0];
-        __threadfence();
-        uint32_t* arrived = reinterpret_cast<uint32_t*>(a.part) + (int64_t)a.BH * FINISH_SPLIT + bh;
-        if (atomicAdd(arrived, 1u) == FINISH_SPLIT - 1) {
-            __threadfence();
-            float v[FINISH_SPLIT];
-#pragma unroll
-            for (int i = 0; i < FINISH_SPLIT; ++i)
-                v[i] = __builtin_bit_cast(float, __atomic_load_n(reinterpret_cast<const uint32_t*>(p + i), __ATOMIC_RELAXED));
-            a.total[bh] = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
-        }
-    }
+    if (tid == 0) a.part[(int64_t)bh * FINISH_SPLIT + part] = red[0];   // `part` is free again once merge_kernel has run
+}
+
+// total[bh] = the ranges' shares added in a fixed tree order
+__global__ void total_kernel(ScoreArgs a) {
+    const int bh = blockIdx.x * blockDim.x + threadIdx.x;
+    if (bh >= a.BH) return;
+    const float* p = a.part + (int64_t)bh * FINISH_SPLIT;
+    a.total[bh] = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
 }
 
 __global__ void fill_zero_kernel(float* p, int64_t count) {
@@ -450,6 +441,7 @@ static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
         return hipGetLastError();
     }
     hipLaunchKernelGGL(finish_kernel, dim3(a.BH, FINISH_SPLIT), dim3(1024), 0, st, a, mode == 0 ? 1 : 0);
+    hipLaunchKernelGGL(total_kernel, dim3((a.BH + 255) / 256), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
