@@ -372,16 +372,16 @@ __device__ __forceinline__ void walk_maxima(const float* m_l, const int32_t (&ix
     }
 }
 
-// Position of the first set bit in the order entry 0 of lane 0, entry 1 of lane 0, ..., entry 0 of lane 1, ...
-// where m[e] has bit j set for entry e of lane j (WALK_RUN if no mask has one).
-__device__ __forceinline__ int walk_first(const uint64_t (&m)[WALK_E]) {
-    int f = WALK_RUN;
+// Position of the first entry for which `p` holds, in the order entry 0 of lane 0, entry 1 of lane 0, ..., entry 0
+// of lane 1, ... (WALK_RUN if it holds nowhere): every lane finds its own first entry, one ballot finds the lane.
+__device__ __forceinline__ int walk_first(const bool (&p)[WALK_E]) {
+    int fe = WALK_E;
 #pragma unroll
-    for (int e = 0; e < WALK_E; ++e) {
-        const int fe = m[e] ? WALK_E * (__ffsll((unsigned long long)m[e]) - 1) + e : WALK_RUN;
-        f = fe < f ? fe : f;
-    }
-    return f;
+    for (int e = WALK_E - 1; e >= 0; --e) fe = p[e] ? e : fe;
+    const uint64_t any = __ballot(fe < WALK_E);
+    if (any == 0ull) return WALK_RUN;
+    const int l = __ffsll((unsigned long long)any) - 1;
+    return WALK_E * l + __builtin_amdgcn_readlane(fe, l);
 }
 
 // grid (BH).  Reads the sorted lists (weights, maxima, indices) and writes taken counts.
@@ -574,13 +574,9 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             ++k;
             if (lane == 0) walk_st(&sync->summed, k);
             // entry e of lane j is pick E * j + e; only picks below `limit` count
-            uint64_t hm[WALK_E];
+            bool hm[WALK_E];
 #pragma unroll
-            for (int e = 0; e < WALK_E; ++e) {
-                const int ne = (limit - e + WALK_E - 1) / WALK_E;       // lanes whose entry e is below limit
-                const uint64_t lanes = ne >= 64 ? ~0ull : ne <= 0 ? 0ull : ((1ull << ne) - 1ull);
-                hm[e] = __ballot(!(x[e] < target)) & lanes;
-            }
+            for (int e = 0; e < WALK_E; ++e) hm[e] = !(x[e] < target) && WALK_E * lane + e < limit;
             const int hit = walk_first(hm);
             const bool reached = hit < WALK_RUN;
             const int taken = reached ? hit + 1 : limit;                    // picks applied
@@ -685,7 +681,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         const bool s_has = S.has, v_has = V.has;
         // entry e of lane j: the decision if the walk has taken E j + e more slashes (iv frozen)
         float gain[WALK_E];
-        uint64_t turn[WALK_E], dead[WALK_E];       // ballots: the pick goes to the other list; no gain is left
+        bool turn[WALK_E], dead[WALK_E];           // the pick goes to the other list; no gain is left
 #pragma unroll
         for (int e = 0; e < WALK_E; ++e) {
             const int i = is + WALK_E * lane + e;
@@ -693,8 +689,8 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             const float dv = __fsub_rn(V.w0, S.pre[e]);
             float cs = __fsub_rn(S.cl[e], (float)iv); if (cs < 1.0f) cs = 1.0f;
             float cv = __fsub_rn(V.l0, (float)i); if (cv < 1.0f) cv = 1.0f;
-            turn[e] = ~__ballot(S.ok[e] && (!v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs)));
-            dead[e] = __ballot(!(ds > 0.f) && (!v_has || !(dv > 0.f)));
+            turn[e] = !(S.ok[e] && (!v_has || __fmul_rn(ds, cv) >= __fmul_rn(dv, cs)));
+            dead[e] = !(ds > 0.f) && (!v_has || !(dv > 0.f));
             gain[e] = ds;
         }
         int run = walk_first(turn);
@@ -709,8 +705,8 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
                 const float ds = __fsub_rn(S.w0, V.pre[e]);
                 float cv = __fsub_rn(V.cl[e], (float)is); if (cv < 1.0f) cv = 1.0f;
                 float cs = __fsub_rn(S.l0, (float)i); if (cs < 1.0f) cs = 1.0f;
-                turn[e] = ~__ballot(V.ok[e] && !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs)));   // set: not a vertical again
-                dead[e] = __ballot(!(dv > 0.f) && (!s_has || !(ds > 0.f)));
+                turn[e] = !(V.ok[e] && !(s_has && __fmul_rn(ds, cv) >= __fmul_rn(dv, cs)));           // true: not a vertical again
+                dead[e] = !(dv > 0.f) && (!s_has || !(ds > 0.f));
                 gain[e] = dv;
             }
             run = walk_first(turn);
