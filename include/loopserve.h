@@ -104,7 +104,8 @@ int ls_score(ls_ctx* ctx, const ls_shape* shape, const void* q_win, const int64_
  *   v_idx [B,Hq,cap_v] int32  selected columns, ascending;   v_cnt [B,Hq] int32
  *   s_idx [B,Hq,cap_s] int32  selected diagonals, ascending; s_cnt [B,Hq] int32
  *   accounted [B,Hq] fp32 or NULL: the loop's final sum.
- * A count larger than its capacity means the list was truncated to the smallest `cap` indices.
+ * A count larger than its capacity means the list was truncated to the smallest `cap` indices
+ * (LS_STAT_S_TRUNCATED / LS_STAT_V_TRUNCATED in the status word).
  * With accounted == NULL the loop stops as soon as the result is decided (when no remaining line
  * has a positive gain every line ends up selected); with accounted != NULL it runs to the end.
  * shape->w and dtype are ignored.  n <= LS_MAX_N.
@@ -121,7 +122,9 @@ int ls_select(ls_ctx* ctx, const ls_shape* shape, float alpha,
  * p_a - b in s_idx), masked entries weighing exactly zero, each allowed cell counted once.
  *
  *   q [B,Hq,n_hat,d]; k, v [B,Hkv,n,d]; index lists as written by ls_select (device memory;
- *   min(cnt, cap) entries are read).
+ *   min(cnt, cap) entries are read).  v_idx must be strictly ascending with entries in [0, n); a head
+ *   whose list is not is computed without its columns and LS_STAT_V_INVALID is set.  s_idx may be in
+ *   any order; entries outside [0, n) are ignored (LS_STAT_S_RANGE).
  * Outputs:
  *   out [B,Hq,n_hat,d] in dtype; a row with no allowed cell is all zeros
  *   lse [B,Hq,n_hat] fp32 or NULL: natural log of the softmax denominator (-inf for an empty row)
@@ -142,6 +145,7 @@ int ls_sparse_prefill(ls_ctx* ctx, const ls_shape* shape, const void* q, const v
  * Outputs:
  *   keep_idx [B,Hkv,budget] int32 ascending; keep_cnt [B,Hkv] = min(budget, len)
  *   k_out, v_out [B,Hkv,budget,d] compacted copies of the kept rows, or NULL
+ * len <= LS_MAX_N (LS_ESHAPE otherwise, before anything is launched).
  */
 int ls_kv_compress(ls_ctx* ctx, const ls_shape* shape, int32_t budget,
                    const void* q_obs, const void* k, const void* v,
@@ -184,11 +188,21 @@ int ls_profile_enable(ls_ctx* ctx, int on);
 int ls_profile_prefill_kernel_ms(ls_ctx* ctx, double* mean_ms, int32_t* launches);
 
 /*
- * Test hook: copies the retention score [B,Hkv,len] fp32 (column sums of the last n_obs rows, summed
- * over each KV group, Sec. 5.2) that the most recent ls_kv_compress call on this context left in
- * the workspace to `dst_device`.  `shape` must be the shape of that call.
+ * Device status word.  Conditions that a kernel can only see while it runs are reported without a
+ * host round trip: the kernel ORs a bit into a word in device memory that belongs to the context, the
+ * call still returns LS_OK, and the outputs are as described for each bit.  ls_poll_status waits for
+ * everything queued on `hip_stream`, writes the word to *host_out (host memory) and clears it; it is
+ * the one call here that synchronises with the host.  (Serves callers of the four entry points above;
+ * no passage of the paper defines it.)
  */
-int ls_debug_copy_compress_score(ls_ctx* ctx, const ls_shape* shape, float* dst_device, void* hip_stream);
+#define LS_STAT_WALK_TIMEOUT 1  /* ls_select: a bounded wait inside the greedy loop gave up; the head concerned reports
+                                   every line selected (v_cnt = s_cnt = n), which still meets the coverage target */
+#define LS_STAT_S_TRUNCATED  2  /* ls_select: s_cnt > cap_s for some head (s_idx holds the smallest cap_s indices) */
+#define LS_STAT_V_TRUNCATED  4  /* ls_select: v_cnt > cap_v for some head */
+#define LS_STAT_S_RANGE      8  /* ls_sparse_prefill: s_idx entries outside [0, n) were ignored */
+#define LS_STAT_V_INVALID   16  /* ls_sparse_prefill: a head's v_idx was not strictly ascending inside [0, n); that
+                                   head's columns were ignored (its diagonals still apply) */
+int ls_poll_status(ls_ctx* ctx, int32_t* host_out, void* hip_stream);
 
 #ifdef __cplusplus
 }

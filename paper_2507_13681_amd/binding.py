@@ -1,4 +1,4 @@
-"""Thin ctypes binding of libloopserve (see include/loopserve.h).
+"""Thin ctypes binding of libloopserve (see include/loopserve.h, include/loopserve_test_hooks.h).
 
 Argument marshalling only: every step of the path runs in the HIP kernels of the library.
 PyTorch supplies device memory and the current stream.  The library must have been built
@@ -20,7 +20,9 @@ LS_MAX_N, LS_MAX_W = 262144, 256
 _lib = None
 
 ENTRY_POINTS = ("ls_workspace_bytes", "ls_create", "ls_destroy", "ls_last_error",
-                "ls_score", "ls_select", "ls_sparse_prefill", "ls_kv_compress")
+                "ls_score", "ls_select", "ls_sparse_prefill", "ls_kv_compress", "ls_poll_status")
+# bits of the device status word (ls_poll_status)
+LS_STAT_WALK_TIMEOUT, LS_STAT_S_TRUNCATED, LS_STAT_V_TRUNCATED, LS_STAT_S_RANGE, LS_STAT_V_INVALID = 1, 2, 4, 8, 16
 
 
 class LsShape(C.Structure):
@@ -65,6 +67,10 @@ def load_library():
     lib.ls_decode_workspace_bytes.argtypes = [sp, i32, i32]
     lib.ls_debug_copy_compress_score.restype = C.c_int
     lib.ls_debug_copy_compress_score.argtypes = [vp, sp, vp, vp]
+    lib.ls_poll_status.restype = C.c_int
+    lib.ls_poll_status.argtypes = [vp, C.POINTER(i32), vp]
+    lib.ls_debug_set_walk_spin_limit.restype = C.c_int
+    lib.ls_debug_set_walk_spin_limit.argtypes = [vp, i32]
     lib.ls_profile_enable.restype = C.c_int
     lib.ls_profile_enable.argtypes = [vp, C.c_int]
     lib.ls_profile_prefill_kernel_ms.restype = C.c_int
@@ -152,6 +158,15 @@ class Context:
         T = 0 if k_t is None else k_t.shape[2]
         self._check(self.lib.ls_decode_attend(self.h, C.byref(shape), k_c.shape[2], T, _ptr(q), _ptr(k_c), _ptr(v_c),
                                               _ptr(cnt), _ptr(k_t), _ptr(v_t), _ptr(out), _ptr(lse), _stream()))
+
+    def ls_poll_status(self) -> int:
+        """Waits for the current stream, returns the context's device status word and clears it."""
+        word = C.c_int32()
+        self._check(self.lib.ls_poll_status(self.h, C.byref(word), _stream()))
+        return word.value
+
+    def debug_set_walk_spin_limit(self, limit: int):
+        self._check(self.lib.ls_debug_set_walk_spin_limit(self.h, limit))
 
     def profile_enable(self, on=True):
         self._check(self.lib.ls_profile_enable(self.h, 1 if on else 0))

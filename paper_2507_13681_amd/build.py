@@ -10,7 +10,7 @@ LIB = os.path.join(_DIR, "libloopserve.so")
 SOURCES = ["ls_api.hip", "ls_score.hip", "ls_select.hip", "ls_prefill.hip", "ls_decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function"]
+         "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def build_library(verbose: bool = False) -> str:

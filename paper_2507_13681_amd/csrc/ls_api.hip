@@ -8,15 +8,23 @@
 #include <utility>
 #include <vector>
 
+#include <mutex>
+
 #include "../../include/loopserve.h"
+#include "../../include/loopserve_test_hooks.h"
 #include "ls_internal.h"
 
-static_assert(ls::TOPB_MAX_LEN >= LS_MAX_N, "top-B kernel must cover the longest context");
+static_assert(ls::TOPB_MAX_LEN == LS_MAX_N, "ls_kv_compress documents LS_MAX_N as its longest cache");
+static_assert(ls::STAT_WALK_TIMEOUT == LS_STAT_WALK_TIMEOUT && ls::STAT_S_TRUNCATED == LS_STAT_S_TRUNCATED &&
+              ls::STAT_V_TRUNCATED == LS_STAT_V_TRUNCATED && ls::STAT_S_RANGE == LS_STAT_S_RANGE &&
+              ls::STAT_V_INVALID == LS_STAT_V_INVALID, "status bits of the kernels and of the header");
 
 struct ls_ctx {
     int device;
     unsigned char* ws;
     size_t ws_bytes;
+    int32_t* status;          // device status word (bits LS_STAT_*), OR-ed into by kernels, read and cleared by ls_poll_status
+    int walk_spin_limit;      // bound of the waits inside walk_kernel (test hook)
     char err[256];
     // optional timing of the sparse attention kernel (ls_profile_*): event pairs on the call's stream
     bool profile;
@@ -39,6 +47,22 @@ int fail(ls_ctx* c, int code, const char* fmt, ...) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Kernel attributes are per device: set once for each device a context is created on, with that device current.
+hipError_t init_device_once(int device) {
+    static std::mutex mu;
+    static std::vector<char> done;
+    std::lock_guard<std::mutex> lock(mu);
+    if ((int)done.size() <= device) done.resize(device + 1, 0);
+    if (done[device]) return hipSuccess;
+    hipError_t e;
+    if ((e = ls::init_score_kernels()) != hipSuccess) return e;
+    if ((e = ls::init_select_kernels()) != hipSuccess) return e;
+    if ((e = ls::init_prefill_kernels()) != hipSuccess) return e;
+    if ((e = ls::init_decode_kernels()) != hipSuccess) return e;
+    done[device] = 1;
+    return hipSuccess;
+}
 
 struct Bump {
     unsigned char* base; size_t cap, off;
@@ -127,9 +151,16 @@ int ls_create(ls_ctx** out, int device, size_t workspace_bytes) {
     ls_ctx* c = new (std::nothrow) ls_ctx();
     if (!c) return LS_EINVAL;
     c->device = device; c->ws = nullptr; c->ws_bytes = workspace_bytes; c->err[0] = 0; c->profile = false;
+    c->status = nullptr; c->walk_spin_limit = ls::WALK_SPIN_DEFAULT;
+    if (init_device_once(device) != hipSuccess) { delete c; return LS_EHIP; }
+    {
+        void* p = nullptr;
+        if (hipMalloc(&p, ALIGN) != hipSuccess || hipMemset(p, 0, ALIGN) != hipSuccess) { if (p) (void)hipFree(p); delete c; return LS_EWORKSPACE; }
+        c->status = static_cast<int32_t*>(p);
+    }
     if (workspace_bytes) {
         void* p = nullptr;
-        if (hipMalloc(&p, workspace_bytes) != hipSuccess) { delete c; return LS_EWORKSPACE; }
+        if (hipMalloc(&p, workspace_bytes) != hipSuccess) { (void)hipFree(c->status); delete c; return LS_EWORKSPACE; }
         c->ws = static_cast<unsigned char*>(p);
     }
     *out = c;
@@ -141,6 +172,7 @@ void ls_destroy(ls_ctx* c) {
     (void)hipSetDevice(c->device);
     for (auto& e : c->events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
     if (c->ws) (void)hipFree(c->ws);
+    if (c->status) (void)hipFree(c->status);
     delete c;
 }
 
@@ -191,7 +223,7 @@ int ls_select(ls_ctx* c, const ls_shape* s, float alpha,
     a.head_w = bp.take<float>(2 * (size_t)a.BH * ls::SELECT_HEAD_LINES); a.head_m = bp.take<float>(2 * (size_t)a.BH * ls::SELECT_HEAD_LINES);
     if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_select: workspace of %zu bytes is too small", c->ws_bytes);
     a.v_idx = v_idx; a.v_cnt = v_cnt; a.s_idx = s_idx; a.s_cnt = s_cnt; a.cap_v = cap_v; a.cap_s = cap_s;
-    a.accounted = accounted;
+    a.accounted = accounted; a.status = c->status; a.spin_limit = c->walk_spin_limit;
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_select: hipSetDevice failed");
     const hipError_t e = ls::run_select(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_select: %s", hipGetErrorString(e));
@@ -232,6 +264,7 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     ls::PlanArgs p{};
     p.n = s->n; p.words = words; p.tab_len = tab_len; p.v_idx = v_idx; p.v_cnt = v_cnt; p.s_idx = s_idx; p.s_cnt = s_cnt;
     p.cap_v = cap_v; p.cap_s = cap_s; p.obits = obits; p.tab = tab; p.hflag = hflag; p.cost = cost; p.pref = pref;
+    p.status = c->status;
     hipError_t e = ls::launch_plan(p, BH, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill(plan): %s", hipGetErrorString(e));
     ls::SchedArgs sa{};
@@ -250,8 +283,8 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     a.obits = obits; a.tab = tab; a.hflag = hflag; a.v_idx = v_idx; a.v_cnt = v_cnt; a.cap_v = cap_v;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (c->profile) {
-        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
-            return fail(c, LS_EHIP, "ls_sparse_prefill: hipEventCreate failed");
+        if (hipEventCreate(&e0) != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: hipEventCreate failed");
+        if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(c, LS_EHIP, "ls_sparse_prefill: hipEventCreate failed"); }
     }
     e = ls::launch_prefill(a, s->dtype, s->d, static_cast<hipStream_t>(stream), e0, e1);
     if (c->profile) c->events.emplace_back(e0, e1);
@@ -264,6 +297,7 @@ int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_o
     if (!c) return LS_EINVAL;
     if (const char* m = check_shape(s, false, true, false)) return fail(c, LS_ESHAPE, "ls_kv_compress: %s", m);
     if (budget <= 0) return fail(c, LS_ESHAPE, "ls_kv_compress: budget must be positive");
+    if (s->n > ls::TOPB_MAX_LEN) return fail(c, LS_ESHAPE, "ls_kv_compress: cache length %lld exceeds LS_MAX_N", (long long)s->n);
     if (ls::score_lines_smem(s->w, s->dtype, s->d, 2) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_kv_compress: w too large for LDS");
     if (!q_obs || !k || !keep_idx || !keep_cnt || (v_out && !v)) return fail(c, LS_EINVAL, "ls_kv_compress: NULL tensor");
     if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
@@ -369,6 +403,25 @@ int ls_profile_prefill_kernel_ms(ls_ctx* c, double* mean_ms, int32_t* launches) 
     }
     *mean_ms = cnt ? tot / cnt : 0.0;
     *launches = cnt;
+    return LS_OK;
+}
+
+int ls_poll_status(ls_ctx* c, int32_t* host_out, void* stream) {
+    if (!c || !host_out) return LS_EINVAL;
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_poll_status: hipSetDevice failed");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t word = 0;
+    // stream-ordered: read the word behind everything queued so far, then clear it
+    if (hipMemcpyAsync(&word, c->status, sizeof(word), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemsetAsync(c->status, 0, sizeof(word), st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess)
+        return fail(c, LS_EHIP, "ls_poll_status: reading the status word failed");
+    *host_out = word;
+    return LS_OK;
+}
+
+int ls_debug_set_walk_spin_limit(ls_ctx* c, int32_t limit) {
+    if (!c) return LS_EINVAL;
+    c->walk_spin_limit = limit < 0 ? ls::WALK_SPIN_DEFAULT : limit;
     return LS_OK;
 }
 

@@ -226,12 +226,14 @@ size_t decode_smem_bytes(int d, int G) {
 template <int D>
 static hipError_t run_decode_t(const DecodeArgs& a, hipStream_t st) {
     const size_t smem = decode_smem_bytes(D, a.G);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_partial_kernel<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((decode_partial_kernel<D>), dim3(a.nsplit, a.B * a.Hkv), dim3(DEC_THREADS), smem, st, a);
     hipLaunchKernelGGL((decode_combine_kernel<D>), dim3(a.B * a.Hq), dim3(D), 0, st, a);
     return hipGetLastError();
+}
+
+hipError_t init_decode_kernels() {
+    const hipError_t e = allow_full_lds(&decode_partial_kernel<128>);
+    return e != hipSuccess ? e : allow_full_lds(&decode_partial_kernel<64>);
 }
 
 hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st) {

@@ -85,13 +85,13 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // that the compiler does not count the transfers among the memory operations it tracks: it cannot tell
 // which LDS bytes a transfer fills and would make every later LDS read wait for all outstanding
 // transfers, serialising a prefetch with the work on the data already there.  A kernel waits for its
-// transfers itself (wait_transfers, then a barrier if other waves read the data).  M0 is used by
-// nothing else in these kernels.
+// transfers itself (wait_transfers, then a barrier if other waves read the data).  M0 is listed as
+// clobbered so that the compiler never keeps a value of its own in M0 across a transfer.
 __device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t voff, uint32_t lds) {   // address = gbase + voff
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory", "m0");
 }
 __device__ __forceinline__ void dma16(const unsigned char* gptr, uint32_t lds) {                    // per-lane address
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(gptr) : "memory", "m0");
 }
 __device__ __forceinline__ void wait_transfers() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

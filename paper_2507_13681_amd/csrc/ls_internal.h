@@ -33,6 +33,8 @@ struct SelectArgs {
     int32_t *v_idx, *v_cnt, *s_idx, *s_cnt;
     int cap_v, cap_s;
     float* accounted;         // may be null
+    int32_t* status;          // device status word of the context (bits LS_STAT_*), OR-ed into
+    int spin_limit;           // bound of every wait between the waves of walk_kernel
 };
 
 constexpr int64_t TOPB_MAX_LEN = 262144;   // longest score row run_topb takes
@@ -57,6 +59,7 @@ struct PlanArgs {
     uint8_t* hflag;           // [BH]
     uint32_t* cost;           // [BH] estimated tiles per row block (for the work queues)
     uint16_t* pref;           // [BH][tab_len + 1] prefix counts of table entries with a selected diagonal
+    int32_t* status;          // device status word of the context (bits LS_STAT_*), OR-ed into
 };
 
 // Work queues of the sparse attention kernel: one list of (head, row block) items per XCD.
@@ -101,6 +104,27 @@ struct DecodeArgs {
     int B, Hq, Hkv, G, cap, T, nsplit, chunk;
     float scale_log2e;
 };
+
+// status bits (mirrors of LS_STAT_* in loopserve.h)
+constexpr int STAT_WALK_TIMEOUT = 1, STAT_S_TRUNCATED = 2, STAT_V_TRUNCATED = 4, STAT_S_RANGE = 8, STAT_V_INVALID = 16;
+constexpr int WALK_SPIN_DEFAULT = 1 << 22;   // never reached in practice (about a second of polling)
+
+// Lets a kernel use all of a compute unit's LDS (160 KB, less what the kernel declares statically) as
+// dynamic LDS; the launches then only have to name the size they need.
+template <typename K>
+inline hipError_t allow_full_lds(K kernel) {
+    hipFuncAttributes fa;
+    hipError_t e = hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               160 * 1024 - (int)fa.sharedSizeBytes);
+}
+
+// Once per device, with that device current: lets every kernel that asks for dynamic LDS use the whole 160 KB.
+hipError_t init_score_kernels();
+hipError_t init_select_kernels();
+hipError_t init_prefill_kernels();
+hipError_t init_decode_kernels();
 
 hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st);
 hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st);

@@ -43,7 +43,8 @@ constexpr int PREFILL_THREADS = 256;
 //   obits : [BH][words + 1] uint32: one zero word, then bit o in word 1 + o/32; words = n/32 rounded up + 8 zero words
 //   tab   : [BH][tab_len] bytes, entry j+1 for j = -1 .. ; bit0 = some diagonal of
 //           [64j-63, 64j+127] is selected, bit1 = all of them are (and none is cut off at 0 or n-1)
-//   hflag : [BH] bytes, bit0 = every diagonal 0..n-1 is selected (the mask is plain causal)
+//   hflag : [BH] bytes, bit0 = every diagonal 0..n-1 is selected (the mask is plain causal),
+//           bit1 = the column list is not strictly ascending inside [0, n): its columns are ignored
 // ---------------------------------------------------------------------------------------------
 // Exclusive prefix sum over the 1024 threads of a workgroup (wave shuffles + one LDS round).
 // `wsum` must hold 16 words; returns the sum of `v` over the threads before this one and, in
@@ -76,7 +77,17 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     const int32_t* si = a.s_idx + (int64_t)bh * a.cap_s;
     for (int i = tid; i < words; i += blockDim.x) sm[i] = 0u;
     if (tid == 0) total_bits = 0;
-    __syncthreads();
+    // The column list must be strictly ascending and inside [0, n) (the attention kernel bisects it and
+    // gathers K / V rows through it): a head whose list is not has its columns ignored (hflag bit 1) and the
+    // context's status word says so.  Diagonals outside [0, n) are skipped below and reported likewise.
+    int nvl = a.v_cnt[bh]; if (nvl > a.cap_v) nvl = a.cap_v; if (nvl < 0) nvl = 0;
+    const int32_t* vl = a.v_idx + (int64_t)bh * a.cap_v;
+    bool v_bad = false, s_bad = false;
+    for (int i = tid; i < nvl; i += blockDim.x) {
+        const int32_t c = vl[i];
+        v_bad = v_bad || c < 0 || c >= n || (i > 0 && vl[i - 1] >= c);
+    }
+    v_bad = __syncthreads_or(v_bad);
     // every diagonal selected (a head the walk gave up sparsifying): the list is 0 .. n-1, checked while it is read
     bool ident = ns == (int)n;
     if (ident) {
@@ -101,6 +112,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
             // plain vector moves) and the run's first lane, and every 16th lane, does the one atomic.  Correct for
             // any order of the list.
             const bool ok = o8[j] >= 0 && o8[j] < n;
+            s_bad = s_bad || (!ok && i0 + j * 1024 < ns);
             const int wd = ok ? o8[j] >> 5 : -1 - (tid & 63);
             uint32_t m = ok ? 1u << (o8[j] & 31) : 0u;
             // value of the lane `off` to the right inside the row (lanes shifted in from outside a row read -2 / 0)
@@ -158,10 +170,13 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     if (e1 == a.tab_len && e0 < a.tab_len) pref[a.tab_len] = (uint16_t)run;
     // head flag and cost estimate: table entries with a selected diagonal (key blocks a late row block
     // visits) plus packed column tiles
+    s_bad = __syncthreads_or(s_bad);
     if (tid == 0) {
-        a.hflag[bh] = (total_bits == (int)n) ? 1 : 0;
+        a.hflag[bh] = ((total_bits == (int)n) ? 1 : 0) | (v_bad ? 2 : 0);
+        if (v_bad) atomicOr(a.status, STAT_V_INVALID);
+        if (s_bad) atomicOr(a.status, STAT_S_RANGE);
         int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
-        if (total_bits == (int)n) nv = 0;
+        if (total_bits == (int)n || v_bad) nv = 0;
         a.cost[bh] = (uint32_t)((int)active_entries + (nv + 63) / 64 + 1);
     }
 }
@@ -225,7 +240,7 @@ __global__ __launch_bounds__(SCHED_THREADS) void sched_kernel(SchedArgs a) {
         const uint16_t* pref = a.pref + (int64_t)bh * (a.tab_len + 1);
         int c = pref[jb + 2] - pref[jb - kb_hi + 1];      // entries jb-kb_hi+1 .. jb+1
         int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
-        if (a.hflag[bh] & 1) nv = 0;
+        if (a.hflag[bh] & 3) nv = 0;
         c += (nv + 63) / 64;
         return c > 4095 ? 4095 : c;
     };
@@ -411,7 +426,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_kernel(PrefillArgs
     // ---- how many selected columns phase 2 gathers (columns beyond the block's last row are invisible)
     int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
     const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
-    if (a.hflag[bh] & 1) nv = 0;                           // every diagonal is selected: phase 1 covers all cells
+    if (a.hflag[bh] & 3) nv = 0;                           // every diagonal is selected (phase 1 covers all cells), or the list is unusable
     if (nv > 0 && (int64_t)vi[nv - 1] > posmax) {          // ascending list: binary search for the first column > posmax
         int lo = 0, hi = nv - 1;
         while (lo < hi) { const int mid = (lo + hi) >> 1; if ((int64_t)vi[mid] > posmax) hi = mid; else lo = mid + 1; }
@@ -778,7 +793,7 @@ __global__ __launch_bounds__(PREFILL_THREADS, 2) void prefill_bf16_kernel(Prefil
     n1 = __builtin_amdgcn_readfirstlane(n1);
     int nv = a.v_cnt[bh]; if (nv > a.cap_v) nv = a.cap_v; if (nv < 0) nv = 0;
     const int32_t* vi = a.v_idx + (int64_t)bh * a.cap_v;
-    if (a.hflag[bh] & 1) nv = 0;                           // every diagonal is selected: phase 1 covers all cells
+    if (a.hflag[bh] & 3) nv = 0;                           // every diagonal is selected (phase 1 covers all cells), or the list is unusable
     if (nv > 0 && (int64_t)vi[nv - 1] > posmax) {          // ascending list: binary search for the first column > posmax
         int lo = 0, hi = nv - 1;
         while (lo < hi) { const int mid = (lo + hi) >> 1; if ((int64_t)vi[mid] > posmax) hi = mid; else lo = mid + 1; }
@@ -1071,9 +1086,6 @@ static bool prefill_bf16_oblds(int words, int tab_len) {
 template <int D, bool OBLDS>
 static hipError_t launch_prefill_bf16_t(const PrefillArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     const size_t smem = prefill_bf16_smem<D>(a.words, a.tab_len, OBLDS);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_bf16_kernel<D, OBLDS>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
     // with events: they take the start and stop time stamps of this dispatch itself, no marker goes into the stream
     if (ev0 && ev1) hipExtLaunchKernelGGL((prefill_bf16_kernel<D, OBLDS>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), (uint32_t)smem, st, ev0, ev1, 0, a);
     else hipLaunchKernelGGL((prefill_bf16_kernel<D, OBLDS>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
@@ -1094,12 +1106,20 @@ static size_t prefill_smem_t(int words, int tab_len) {
 template <typename T, int D>
 static hipError_t launch_prefill_t(const PrefillArgs& a, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
     const size_t smem = prefill_smem_t<T, D>(a.words, a.tab_len);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<T, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
     if (ev0 && ev1) hipExtLaunchKernelGGL((prefill_kernel<T, D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), (uint32_t)smem, st, ev0, ev1, 0, a);
     else hipLaunchKernelGGL((prefill_kernel<T, D>), dim3(persistent_grid(a)), dim3(PREFILL_THREADS), smem, st, a);
     return hipGetLastError();
+}
+
+hipError_t init_prefill_kernels() {
+    hipError_t e;
+    if ((e = allow_full_lds(&prefill_bf16_kernel<128, true>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&prefill_bf16_kernel<128, false>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&prefill_bf16_kernel<64, true>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&prefill_bf16_kernel<64, false>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&prefill_kernel<float, 128>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&prefill_kernel<float, 64>)) != hipSuccess) return e;
+    return allow_full_lds(&plan_kernel);
 }
 
 size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len) {
@@ -1111,9 +1131,6 @@ size_t prefill_smem_bytes(int dtype, int d, int words, int tab_len) {
 
 hipError_t launch_plan(const PlanArgs& a, int BH, hipStream_t st) {
     const size_t smem = (size_t)a.words * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&plan_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(plan_kernel, dim3(BH), dim3(1024), smem, st, a);
     return hipGetLastError();
 }

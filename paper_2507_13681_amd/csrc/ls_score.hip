@@ -413,36 +413,40 @@ static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.nkb, a.B * a.Hkv);
     const int wpad = ((a.w + 31) / 32) * 32;
     const size_t qbytes = (size_t)wpad * D * Elem<T>::bytes;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_kernel<T, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)qbytes);
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((stats_kernel<T, D>), grid, dim3(SCORE_THREADS), qbytes, st, a);
     const int rows = a.BH * a.w;
     hipLaunchKernelGGL(merge_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, a, rows);
     const size_t smem = (mode == 0 ? (size_t)wpad * (SB + 1) * 4 : 0) + (size_t)wpad * 8 + (size_t)wpad * 4 + qbytes;
     if (mode == 0) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 0>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((lines_kernel<T, D, 0>), grid, dim3(SCORE_THREADS), smem, st, a);
     } else if (mode == 1) {
         const int64_t cnt = (int64_t)a.BH * a.n;
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.slash, cnt);
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.smax, cnt);
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((lines_kernel<T, D, 1>), grid, dim3(SCORE_THREADS), smem, st, a);
     } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lines_kernel<T, D, 2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((lines_kernel<T, D, 2>), grid, dim3(SCORE_THREADS), smem, st, a);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(finish_kernel, dim3(a.BH, FINISH_SPLIT), dim3(1024), 0, st, a, mode == 0 ? 1 : 0);
     hipLaunchKernelGGL(total_kernel, dim3((a.BH + 255) / 256), dim3(256), 0, st, a);
     return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t init_score_t() {
+    hipError_t e;
+    if ((e = allow_full_lds(&stats_kernel<T, D>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&lines_kernel<T, D, 0>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&lines_kernel<T, D, 1>)) != hipSuccess) return e;
+    return allow_full_lds(&lines_kernel<T, D, 2>);
+}
+hipError_t init_score_kernels() {
+    hipError_t e;
+    if ((e = init_score_t<bf16_t, 128>()) != hipSuccess) return e;
+    if ((e = init_score_t<bf16_t, 64>()) != hipSuccess) return e;
+    if ((e = init_score_t<float, 128>()) != hipSuccess) return e;
+    return init_score_t<float, 64>();
 }
 
 hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t st) {

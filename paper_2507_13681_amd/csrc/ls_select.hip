@@ -299,7 +299,6 @@ constexpr int WALK_NBLK = 4;                   // blocks of a list resident in L
 constexpr int WALK_CAP = WALK_BLK * WALK_NBLK;
 constexpr int WALK_EB = WALK_BLK / 64;         // entries per lane when a block's prefix sums are added
 static_assert(WALK_EB % 2 == 0 && WALK_RUN <= WALK_BLK, "a run never reaches beyond the block after the head's");
-constexpr int WALK_SPIN_LIMIT = 1 << 22;       // bound of every wait between the waves (never reached; about a second)
 
 // The resident part of one sorted list, indexed by sorted position modulo WALK_CAP: weights, line lengths, and
 // pre[p] = the overlap sum when the first p lines of the list have been taken.
@@ -406,6 +405,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     const int n = (int)a.n;
     const int nblk = (n + WALK_BLK - 1) / WALK_BLK;
     const int64_t nh = a.n_hat;
+    const int spin_limit = a.spin_limit;       // bound of every wait between the waves
     const int64_t seg_s = ((int64_t)0 * a.BH + bh) * a.n, seg_v = ((int64_t)1 * a.BH + bh) * a.n;
 
     if (threadIdx.x == 0) {
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         while (walk_ld(&sync->done) == 0 && b < nblk) {
             if (b > walk_ld(&sync->cur[l]) + WALK_NBLK - 1) {
                 __builtin_amdgcn_s_sleep(2);
-                if (++spins > WALK_SPIN_LIMIT) { walk_st(&sync->err, 1); break; }
+                if (++spins > spin_limit) { walk_st(&sync->err, 1); break; }
                 continue;
             }
             spins = 0;
@@ -498,7 +498,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         while (walk_ld(&sync->done) == 0 && b < nblk) {
             if (b > walk_ld(&sync->cur[l]) + WALK_NBLK - 1) {
                 __builtin_amdgcn_s_sleep(2);
-                if (++spins > WALK_SPIN_LIMIT) { walk_st(&sync->err, 1); break; }
+                if (++spins > spin_limit) { walk_st(&sync->err, 1); break; }
                 continue;
             }
             spins = 0;
@@ -536,7 +536,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
                     failed = !have && walk_ld(&sync->err) != 0;
                     break;
                 }
-                if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
+                if (++spins > spin_limit || walk_ld(&sync->err)) { failed = true; break; }
                 __builtin_amdgcn_s_sleep(1);
             }
             if (!have) break;                  // both lists were used up (or a wait ran into its bound)
@@ -594,9 +594,12 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
         if (lane == 0) {
             walk_st(&sync->stop, 1);
             if (failed) walk_st(&sync->err, 1);
-            // a wait that ran into its bound (never observed) reports an empty selection
-            a.s_cnt[bh] = failed ? 0 : all ? n : cnt_s;
-            a.v_cnt[bh] = failed ? 0 : all ? n : cnt_v;
+            // A wait that ran into its bound (never observed with the default bound) reports the conservative
+            // result, every line selected: the coverage target of Alg. 2 still holds for it, and the context's
+            // status word tells the caller.
+            a.s_cnt[bh] = (failed || all) ? n : cnt_s;
+            a.v_cnt[bh] = (failed || all) ? n : cnt_v;
+            if (failed) atomicOr(a.status, STAT_WALK_TIMEOUT);
             if (a.accounted) a.accounted[bh] = sum;
         }
         return;
@@ -618,7 +621,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             have = st < su ? st : su;
             if (have >= want) break;
             __builtin_amdgcn_s_sleep(1);
-            if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
+            if (++spins > spin_limit || walk_ld(&sync->err)) { failed = true; break; }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         return have;
@@ -726,7 +729,7 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
             if (__builtin_amdgcn_readfirstlane((int)(ss >> 32))) { stopped = true; break; }
             if (published - __builtin_amdgcn_readfirstlane((int)ss) < WALK_RING) break;
             __builtin_amdgcn_s_sleep(1);
-            if (++spins > WALK_SPIN_LIMIT || walk_ld(&sync->err)) { failed = true; break; }
+            if (++spins > spin_limit || walk_ld(&sync->err)) { failed = true; break; }
         }
         if (stopped || failed) break;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
@@ -763,6 +766,7 @@ __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
     const int cnt = list == 0 ? a.s_cnt[bh] : a.v_cnt[bh];
     int32_t* out = list == 0 ? a.s_idx + (int64_t)bh * a.cap_s : a.v_idx + (int64_t)bh * a.cap_v;
     const int cap = list == 0 ? a.cap_s : a.cap_v;
+    if (tid == 0 && cnt > cap) atomicOr(a.status, list == 0 ? STAT_S_TRUNCATED : STAT_V_TRUNCATED);
     if (cnt >= n) {                                        // every line was taken: the list is 0 .. n-1
         for (int64_t i = tid; i < n && i < cap; i += 1024) out[i] = (int32_t)i;
         return;
@@ -1004,15 +1008,21 @@ __global__ void gather_rows_kernel(const unsigned char* src, unsigned char* dst,
 template <int SEG>
 static hipError_t launch_sort(const SelectArgs& a, hipStream_t st) {
     const int nseg = (int)((a.n + SEG - 1) / SEG);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sort_seg_kernel<SEG>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sort_lds_bytes(SEG));
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sort_merge_kernel<SEG>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 2 * SEG * 4);
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sort_seg_kernel<SEG>, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), sort_lds_bytes(SEG), st, a);
     hipLaunchKernelGGL(sort_merge_kernel<SEG>, dim3(nseg, 2, a.BH), dim3(SORT_THREADS), 2 * SEG * 4, st, a);
-    return hipSuccess;
+    return hipGetLastError();
+}
+
+hipError_t init_select_kernels() {
+    hipError_t e;
+    if ((e = allow_full_lds(&sort_seg_kernel<SORT_SEG_MIN>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&sort_seg_kernel<4096>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&sort_seg_kernel<SORT_SEG_MAX>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&sort_merge_kernel<SORT_SEG_MIN>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&sort_merge_kernel<4096>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&sort_merge_kernel<SORT_SEG_MAX>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&walk_kernel)) != hipSuccess) return e;
+    return allow_full_lds(&emit_kernel);
 }
 
 hipError_t run_select(const SelectArgs& a, hipStream_t st) {
@@ -1023,14 +1033,8 @@ hipError_t run_select(const SelectArgs& a, hipStream_t st) {
                  : want <= 4096         ? launch_sort<4096>(a, st)
                                         : launch_sort<SORT_SEG_MAX>(a, st);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&walk_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)WALK_LDS_BYTES);
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(walk_kernel, dim3(a.BH), dim3(WALK_THREADS), WALK_LDS_BYTES, st, a);
     const size_t smem = (size_t)((a.n + 31) / 32) * 4;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&emit_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(emit_kernel, dim3(2, a.BH), dim3(1024), smem, st, a);
     return hipGetLastError();
 }

@@ -36,9 +36,14 @@ class Pipeline:
                            out["v_idx"], out["v_cnt"], out["s_idx"], out["s_cnt"], out["accounted"])
         return out
 
-    def prefill(self, sel, want_lse=True):
+    def prefill(self, sel, want_lse=True, sentinel=False):
+        """sentinel: pre-fill the outputs with NaN, so that a row no work item wrote stays recognisable."""
         out = torch.empty_like(self.q)
         lse = torch.empty(self.q.shape[:3], dtype=torch.float32, device="cuda") if want_lse else None
+        if sentinel:
+            out.fill_(float("nan"))
+            if lse is not None:
+                lse.fill_(float("nan"))
         self.ctx.ls_sparse_prefill(self.shape, self.q, self.k, self.v, sel["v_idx"], sel["v_cnt"], sel["s_idx"],
                                    sel["s_cnt"], out, lse)
         return out, lse

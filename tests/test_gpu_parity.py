@@ -284,6 +284,10 @@ def test_argument_errors_are_reported():
     big = binding.make_shape(1, 4, 2, 64, 1 << 20, 64, 16, "bf16")
     with pytest.raises(binding.LoopServeError, match="LS_MAX_N"):
         ctx.ls_sparse_prefill(big, q, k, k, sel["v_idx"], sel["v_cnt"], sel["s_idx"], sel["s_cnt"], q)
+    keep_idx = torch.zeros(1, 2, 8, dtype=torch.int32, device="cuda")
+    keep_cnt = torch.zeros(1, 2, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.LoopServeError, match="LS_MAX_N"):      # longer than the top-B kernels take: refused on the host
+        ctx.ls_kv_compress(big, 8, q[:, :, -16:].contiguous(), k, None, keep_idx, keep_cnt)
     small = binding.Context(workspace=1024)
     with pytest.raises(binding.LoopServeError, match="workspace"):
         small.ls_score(shape, q[:, :, -16:].contiguous(), k, sc["vert"], sc["slash"], sc["vmax"], sc["smax"], sc["total"])

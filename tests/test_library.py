@@ -19,15 +19,19 @@ def lib():
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "loopserve.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ls_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+            names.update(re.findall(r"\b(ls_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_exported(lib):
     names = _declared()
     assert {"ls_score", "ls_select", "ls_sparse_prefill", "ls_kv_compress", "ls_create", "ls_destroy",
-            "ls_last_error", "ls_workspace_bytes"} <= set(names)
+            "ls_last_error", "ls_workspace_bytes", "ls_poll_status", "ls_debug_set_walk_spin_limit"} <= set(names)
     raw = ctypes.CDLL(build.LIB)
     for n in names:
         assert hasattr(raw, n), n
