@@ -68,7 +68,8 @@ size_t ls_workspace_bytes(const ls_shape* shape, int32_t budget);
  * here, freed by ls_destroy).  The context can serve any shape whose ls_workspace_bytes fits. */
 int ls_create(ls_ctx** out, int device, size_t workspace_bytes);
 void ls_destroy(ls_ctx* ctx);
-/* Message of the last failing call on this context (never NULL; not thread-safe). */
+/* Message of the last failing call on this context (never NULL; not thread-safe); with ctx == NULL, of the
+ * last failing call that takes no context (ls_kv_compress_static). */
 const char* ls_last_error(const ls_ctx* ctx);
 
 /*
@@ -150,6 +151,26 @@ int ls_sparse_prefill(ls_ctx* ctx, const ls_shape* shape, const void* q, const v
 int ls_kv_compress(ls_ctx* ctx, const ls_shape* shape, int32_t budget,
                    const void* q_obs, const void* k, const void* v,
                    int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* hip_stream);
+
+/*
+ * ls_kv_compress_static -- ls_kv_compress for callers that cannot allocate device memory or hold a
+ * context: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs, limits and results as ls_kv_compress on GPU `device`, but no ls_ctx: its
+ * intermediate results (softmax partials of the observation rows, the per-group score, the radix
+ * histograms and counts of the top-B selection) live in a fixed block of device memory that is part of
+ * the library image, ls_static_scratch_bytes() = LS_STATIC_SCRATCH_BYTES bytes on every GPU the
+ * library is used on, held until the process ends.  The call allocates and frees nothing (no hipMalloc,
+ * hipFree or allocating library routine) and clears what it needs with kernels of its own.
+ * A shape that needs more scratch than that (its ls_workspace_bytes says how much) is refused with
+ * LS_EWORKSPACE before anything is launched; ls_last_error(NULL) describes the failure.
+ * All calls on one GPU share that GPU's block: calls that overlap in time on one GPU (different streams
+ * or threads) race and must be ordered by the caller.
+ */
+#define LS_STATIC_SCRATCH_BYTES (16u << 20)
+size_t ls_static_scratch_bytes(void);
+int ls_kv_compress_static(int device, const ls_shape* shape, int32_t budget,
+                          const void* q_obs, const void* k, const void* v,
+                          int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* hip_stream);
 
 /*
  * ls_decode_attend -- Alg. 3, the Decoding step (Sec. 5.2) seen from one attention layer: the newest

@@ -61,6 +61,10 @@ def load_library():
     lib.ls_sparse_prefill.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.ls_kv_compress.restype = C.c_int
     lib.ls_kv_compress.argtypes = [vp, sp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ls_kv_compress_static.restype = C.c_int
+    lib.ls_kv_compress_static.argtypes = [C.c_int, sp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ls_static_scratch_bytes.restype = C.c_size_t
+    lib.ls_static_scratch_bytes.argtypes = []
     lib.ls_decode_attend.restype = C.c_int
     lib.ls_decode_attend.argtypes = [vp, sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ls_decode_workspace_bytes.restype = C.c_size_t
@@ -178,6 +182,19 @@ class Context:
 
     def debug_compress_score(self, shape, dst):
         self._check(self.lib.ls_debug_copy_compress_score(self.h, C.byref(shape), _ptr(dst), _stream()))
+
+
+def ls_kv_compress_static(shape, budget, q_obs, k, v, keep_idx, keep_cnt, k_out=None, v_out=None, device=0):
+    """ls_kv_compress without a context, on the library's static scratch (allocates nothing)."""
+    lib = load_library()
+    rc = lib.ls_kv_compress_static(device, C.byref(shape), budget, _ptr(q_obs), _ptr(k), _ptr(v), _ptr(keep_idx),
+                                   _ptr(keep_cnt), _ptr(k_out), _ptr(v_out), _stream())
+    if rc != 0:
+        raise LoopServeError(f"{lib.ls_last_error(None).decode()} (status {rc})")
+
+
+def static_scratch_bytes() -> int:
+    return int(load_library().ls_static_scratch_bytes())
 
 
 # -- convenience: allocate outputs with torch and run one call ----------------------------------

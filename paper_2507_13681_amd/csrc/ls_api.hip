@@ -48,14 +48,27 @@ int fail(ls_ctx* c, int code, const char* fmt, ...) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Kernel attributes are per device: set once for each device a context is created on, with that device current.
+// Scratch of the entry point that allocates nothing (ls_kv_compress_static): a fixed block of device memory
+// that is part of the loaded code object.  Every GPU the library runs on holds its own copy at its own
+// address until the process ends; host code reaches it only through the address that hipGetSymbolAddress
+// returns on that device (scratch_on[device]), never through the array's name.
+constexpr size_t STATIC_SCRATCH_BYTES = LS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+std::vector<unsigned char*> scratch_on;      // per device, filled by init_device_once
+char static_err[256] = "";                   // last error of a call that has no context
+
+// Kernel attributes and the scratch address are per device: set once for each device the library is used on,
+// with that device current.
 hipError_t init_device_once(int device) {
     static std::mutex mu;
     static std::vector<char> done;
     std::lock_guard<std::mutex> lock(mu);
-    if ((int)done.size() <= device) done.resize(device + 1, 0);
+    if ((int)done.size() <= device) { done.resize(device + 1, 0); scratch_on.resize(device + 1, nullptr); }
     if (done[device]) return hipSuccess;
     hipError_t e;
+    unsigned char* sp = nullptr;
+    if ((e = hipGetSymbolAddress(reinterpret_cast<void**>(&sp), HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    scratch_on[device] = sp;
     if ((e = ls::init_score_kernels()) != hipSuccess) return e;
     if ((e = ls::init_select_kernels()) != hipSuccess) return e;
     if ((e = ls::init_prefill_kernels()) != hipSuccess) return e;
@@ -176,7 +189,7 @@ void ls_destroy(ls_ctx* c) {
     delete c;
 }
 
-const char* ls_last_error(const ls_ctx* c) { return c ? c->err : "context is NULL"; }
+const char* ls_last_error(const ls_ctx* c) { return c ? c->err : static_err; }
 
 int ls_score(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_pos, const void* k,
              float* vert, float* slash, float* vmax, float* smax, float* total, void* stream) {
@@ -292,44 +305,82 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     return LS_OK;
 }
 
-int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_obs, const void* k, const void* v,
+namespace {
+// Where a call's errors go: the context's message buffer, or the library's own for calls without a context.
+struct ErrSink {
+    ls_ctx* c;
+    int operator()(int code, const char* fmt, ...) const {
+        char* dst = c ? c->err : static_err;
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(dst, 256, fmt, ap);
+        va_end(ap);
+        return code;
+    }
+};
+
+// ls_kv_compress on an explicit scratch block (the context's workspace, or the static scratch)
+int kv_compress_on(const ErrSink& fail, const char* who, int device, unsigned char* ws, size_t ws_bytes,
+                   const ls_shape* s, int32_t budget, const void* q_obs, const void* k, const void* v,
                    int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* stream) {
-    if (!c) return LS_EINVAL;
-    if (const char* m = check_shape(s, false, true, false)) return fail(c, LS_ESHAPE, "ls_kv_compress: %s", m);
-    if (budget <= 0) return fail(c, LS_ESHAPE, "ls_kv_compress: budget must be positive");
-    if (s->n > ls::TOPB_MAX_LEN) return fail(c, LS_ESHAPE, "ls_kv_compress: cache length %lld exceeds LS_MAX_N", (long long)s->n);
-    if (ls::score_lines_smem(s->w, s->dtype, s->d, 2) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_kv_compress: w too large for LDS");
-    if (!q_obs || !k || !keep_idx || !keep_cnt || (v_out && !v)) return fail(c, LS_EINVAL, "ls_kv_compress: NULL tensor");
+    if (const char* m = check_shape(s, false, true, false)) return fail(LS_ESHAPE, "%s: %s", who, m);
+    if (budget <= 0) return fail(LS_ESHAPE, "%s: budget must be positive", who);
+    if (s->n > ls::TOPB_MAX_LEN) return fail(LS_ESHAPE, "%s: cache length %lld exceeds LS_MAX_N", who, (long long)s->n);
+    if (ls::score_lines_smem(s->w, s->dtype, s->d, 2) > 160 * 1024) return fail(LS_ESHAPE, "%s: w too large for LDS", who);
+    if (!q_obs || !k || !keep_idx || !keep_cnt || (v_out && !v)) return fail(LS_EINVAL, "%s: NULL tensor", who);
     if (!aligned16(q_obs) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
-        return fail(c, LS_EINVAL, "ls_kv_compress: misaligned tensor");
+        return fail(LS_EINVAL, "%s: misaligned tensor", who);
     ls::ScoreArgs a{};
     a.q = q_obs; a.k = k; a.q_pos = nullptr; a.n = s->n; a.w = s->w; a.G = s->Hq / s->Hkv; a.Hq = s->Hq;
     a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
     const int BK = s->B * s->Hkv;
-    Bump bp{c->ws, c->ws_bytes, 0};
+    Bump bp{ws, ws_bytes, 0};
     a.part = bp.take<float>(part_floats(s));
     a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
     a.gscore = bp.take<float>((size_t)BK * (size_t)a.n);
     uint32_t* tb_scratch = bp.take<uint32_t>(ls::topb_scratch_words(BK, s->n));
-    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_kv_compress: workspace of %zu bytes is too small", c->ws_bytes);
-    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress: hipSetDevice failed");
+    if (!bp.ok()) return fail(LS_EWORKSPACE, "%s: needs %zu bytes of scratch, %zu are there", who, ws_compress(s), ws_bytes);
+    if (hipSetDevice(device) != hipSuccess) return fail(LS_EHIP, "%s: hipSetDevice failed", who);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = ls::run_score(a, s->dtype, s->d, 2, st);
-    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(score): %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(LS_EHIP, "%s(score): %s", who, hipGetErrorString(e));
     ls::TopbArgs t{};
     t.score = a.gscore; t.len = s->n; t.budget = budget; t.keep_idx = keep_idx; t.keep_cnt = keep_cnt;
     e = ls::run_topb(t, BK, tb_scratch, st);
-    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(topb): %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(LS_EHIP, "%s(topb): %s", who, hipGetErrorString(e));
     const int row_bytes = s->d * (s->dtype == LS_BF16 ? 2 : 4);
     if (k_out) {
         e = ls::run_gather_rows(k, k_out, keep_idx, keep_cnt, BK, s->n, budget, row_bytes, st);
-        if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(gather k): %s", hipGetErrorString(e));
+        if (e != hipSuccess) return fail(LS_EHIP, "%s(gather k): %s", who, hipGetErrorString(e));
     }
     if (v_out) {
         e = ls::run_gather_rows(v, v_out, keep_idx, keep_cnt, BK, s->n, budget, row_bytes, st);
-        if (e != hipSuccess) return fail(c, LS_EHIP, "ls_kv_compress(gather v): %s", hipGetErrorString(e));
+        if (e != hipSuccess) return fail(LS_EHIP, "%s(gather v): %s", who, hipGetErrorString(e));
     }
     return LS_OK;
+}
+}  // namespace
+
+int ls_kv_compress(ls_ctx* c, const ls_shape* s, int32_t budget, const void* q_obs, const void* k, const void* v,
+                   int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* stream) {
+    if (!c) return LS_EINVAL;
+    return kv_compress_on(ErrSink{c}, "ls_kv_compress", c->device, c->ws, c->ws_bytes, s, budget, q_obs, k, v,
+                          keep_idx, keep_cnt, k_out, v_out, stream);
+}
+
+size_t ls_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int ls_kv_compress_static(int device, const ls_shape* s, int32_t budget, const void* q_obs, const void* k, const void* v,
+                          int32_t* keep_idx, int32_t* keep_cnt, void* k_out, void* v_out, void* stream) {
+    const ErrSink fail{nullptr};
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev)
+        return fail(LS_EHIP, "ls_kv_compress_static: no GPU %d", device);
+    if (hipSetDevice(device) != hipSuccess) return fail(LS_EHIP, "ls_kv_compress_static: hipSetDevice failed");
+    const hipError_t e = init_device_once(device);      // first call on this device: kernel attributes, scratch address
+    if (e != hipSuccess) return fail(LS_EHIP, "ls_kv_compress_static: %s", hipGetErrorString(e));
+    return kv_compress_on(fail, "ls_kv_compress_static", device, scratch_on[device], STATIC_SCRATCH_BYTES, s, budget,
+                          q_obs, k, v, keep_idx, keep_cnt, k_out, v_out, stream);
 }
 
 namespace {
