@@ -23,10 +23,6 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_FP32_MFMA_TFLOPS = 157.3
-# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/prefill_bf16_kernel_multiturn_32k_counters.md (scaled by the copy-probe factors 2.00 / 1.00).
-# Counters cannot be read inside a timed run, so this is the recorded figure for the default workload only.
-MEASURED_TRAFFIC_BYTES = {("multiturn_32k", 0.95): 2.33e9}
 
 
 def per_row_cells(n, n_hat, rows_a, v_sel, s_sel):
@@ -53,7 +49,9 @@ def main():
     ap.add_argument("--n-obs", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (see profiles/)")
+                    help="HBM bytes per launch of the dominant kernel, measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                         "this same command (see profiles/); counters cannot be read inside a timed run, so roofline.traffic is "
+                         "null unless this is given")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB MiB (10 launches): calibrates the rocprofv3 FETCH_SIZE / "
                          "WRITE_SIZE counters against a kernel of known traffic")
@@ -184,6 +182,33 @@ def main():
 
     sel_h = {a: b.cpu().numpy() for a, b in sel.items() if b is not None}
     cells = metrics.selection_cells(cfg.n, cfg.n_hat, sel_h)
+
+    # What each kind of head costs the attention kernel (outside the timed region): the launch is repeated with the
+    # lists of one kind emptied, and the kind is charged the time the full launch takes longer than that one.
+    def kernel_ms_with(v_cnt, s_cnt, reps=3):
+        ctx.profile_enable(True)
+        for _ in range(reps):
+            ctx.ls_sparse_prefill(shape, qd, kd, vd, sel["v_idx"], v_cnt, sel["s_idx"], s_cnt, out, lse)
+        torch.cuda.synchronize()
+        ms, _ = ctx.profile_prefill_kernel_ms()
+        ctx.profile_enable(False)
+        return ms
+
+    nvd, nsd = sel["v_cnt"], sel["s_cnt"]
+    kind_masks = {"exhausted": (nvd >= cfg.n) & (nsd >= cfg.n), "slash_only": (nvd == 0) & (nsd > 0),
+                  "vertical_only": (nsd == 0) & (nvd > 0)}
+    kind_masks["mixed"] = (nvd > 0) & (nsd > 0) & ~kind_masks["exhausted"]
+    t_all = kernel_ms_with(nvd, nsd)
+    by_kind = {}
+    for kname, m in kind_masks.items():
+        if int(m.sum()) == 0:
+            continue
+        zero = torch.zeros_like(nvd)
+        t_without = kernel_ms_with(torch.where(m, zero, nvd), torch.where(m, zero, nsd))
+        kc = int(cells[m.cpu().numpy()].sum())
+        ms_k = max(t_all - t_without, 1e-6)
+        by_kind[kname] = {"heads": int(m.sum()), "selected_cells": kc, "kernel_ms_share": round(ms_k, 4),
+                          "effective_tflops": round(4.0 * cfg.d * kc / (ms_k * 1e-3) / 1e12, 1)}
     total_cells = int(cells.sum())
     dense_cells = cfg.B * cfg.Hq * metrics.causal_cells(cfg.n, cfg.n_hat)
     flops = 4.0 * cfg.d * total_cells                     # 2 d for q.k and 2 d for p.v per allowed cell
@@ -205,10 +230,11 @@ def main():
         "heads": {"dense": int(((nv >= cfg.n) & (ns >= cfg.n)).sum()), "slash_only": int(((nv == 0) & (ns > 0)).sum()),
                   "vertical_only": int(((ns == 0) & (nv > 0)).sum()),
                   "mixed": int(((ns > 0) & (nv > 0) & ~((nv >= cfg.n) & (ns >= cfg.n))).sum())},
+        "by_head_kind": by_kind,
         "ms_per_call": {a: round(b, 4) for a, b in br.items()},
         "wall_s": round(wall, 3),
         "roofline": {"kernel": "prefill_bf16_kernel" if cfg.dtype == "bf16" else "prefill_kernel", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get((cfg.name, alpha)),
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes,
                      "kernel_ms": round(kern_ms, 4), "launches": launches},
         "paper_context": "no speed-up printed in the paper's text; its machine: 1x H100 80GB + 8-core Xeon Gold 6542Y",
     }

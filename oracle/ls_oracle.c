@@ -19,6 +19,8 @@
  *                a vertical line is a key column, a slash line is a diagonal.
  *   lso_walk     Alg. 2, the while-loop (greedy selection with overlap bound).
  *   lso_select   Alg. 2, Desc_Sort of both line lists followed by the walk.
+ *   lso_window / lso_select_exact   the window matrix of Alg. 2 itself, and the same loop
+ *                with the overlap of a candidate line counted cell by cell.
  *   lso_attend   masked attention Softmax(QK^T/sqrt(d_k) - c(1-M)) V of
  *                Sec. 2.2 with M the union of selected columns and diagonals,
  *                restricted to the rows of the newest turn (Sec. 5, Step 1).
@@ -236,6 +238,151 @@ int lso_select_all(int64_t heads, int64_t n, int64_t n_hat, float alpha,
         int r = lso_select(n, n_hat, alpha, vert + h * n, slash + h * n, vmax + h * n, smax + h * n,
                            total[h], v_idx + h * cap_v, v_cnt + h, cap_v,
                            s_idx + h * cap_s, s_cnt + h, cap_s, accounted + h, before_last + h);
+        if (r) rc = r;
+    }
+    return rc;
+}
+
+/* ----------------------------------------------------------------- O2x --- */
+
+/*
+ * The window attention matrix itself (Alg. 2, the softmax step), kept instead of
+ * only its line sums: a_win [B,Hq,w,n] floats, A[t][j] for keys j <= p_t and 0
+ * beyond (causal).  Same arguments as lso_score.
+ */
+int lso_window(int B, int Hq, int Hkv, int d, int64_t n, int w, double scale,
+               const float *q_win, const int64_t *q_pos, const float *k, float *a_win)
+{
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || d <= 0 || n <= 0 || w <= 0) return -1;
+    const int G = Hq / Hkv;
+    int rc = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * Hq; ++bh) {
+        const int b = bh / Hq, h = bh % Hq, kvh = h / G;
+        const float *K = k + ((int64_t)b * Hkv + kvh) * n * d;
+        const float *Q = q_win + (int64_t)bh * w * d;
+        double *logit = malloc(n * sizeof(double));
+        if (!logit) { rc = -2; continue; }
+        for (int t = 0; t < w; ++t) {
+            float *row = a_win + ((int64_t)bh * w + t) * n;
+            const int64_t p = q_pos ? q_pos[t] : n - w + t;
+            if (p < 0 || p >= n) { rc = -3; break; }
+            double mx = -INFINITY, den = 0.0;
+            for (int64_t j = 0; j <= p; ++j) {
+                double s = 0.0;
+                for (int c = 0; c < d; ++c) s += (double)Q[(int64_t)t * d + c] * (double)K[j * d + c];
+                logit[j] = s * scale;
+                if (logit[j] > mx) mx = logit[j];
+            }
+            for (int64_t j = 0; j <= p; ++j) den += exp(logit[j] - mx);
+            for (int64_t j = 0; j < n; ++j) row[j] = j <= p ? (float)(exp(logit[j] - mx) / den) : 0.0f;
+        }
+        free(logit);
+    }
+    return rc;
+}
+
+/*
+ * Alg. 2 with the marginal contribution of a line taken exactly (Sec. 5.1 describes
+ * the quantities compared in the loop as marginal contributions; the listing bounds
+ * the part of a line that is already covered by the sum of w^max of the lines taken
+ * from the other list).  Here the covered part of a candidate is added up cell by
+ * cell: a diagonal o and a column b share the cell of the scored row at position
+ * b + o, if there is one, so
+ *     overlap(slash o)  = sum over scored rows t with key c = p_t - o >= 0 and c selected     of A[t][c]
+ *     overlap(column b) = sum over scored rows t with o = p_t - b >= 0 and o selected         of A[t][b]
+ * (added in row order in double precision, rounded once to binary32).  Everything
+ * else is the loop of lso_walk: gain = weight - overlap, cost = max(1, length - lines
+ * taken from the other list), the slash is taken when gain_s * cost_v >= gain_v * cost_s,
+ * the head of the chosen list is removed, the loop ends when the sum reaches
+ * alpha * total or both lists are empty.  Gains are never negative here, and the
+ * final sum is the weight of the union of the selected lines on the scored rows.
+ *
+ * a_win [w,n] is the head's window matrix (lso_window), q_pos[w] the rows' positions
+ * (NULL: n-w .. n-1), vert / slash [n] the line weights the lists are ordered by.
+ */
+int lso_select_exact(int64_t n, int64_t n_hat, int w, float alpha,
+                     const float *a_win, const int64_t *q_pos,
+                     const float *vert, const float *slash, float total,
+                     int32_t *v_idx, int32_t *v_cnt, int64_t cap_v,
+                     int32_t *s_idx, int32_t *s_cnt, int64_t cap_s,
+                     float *accounted, float *before_last)
+{
+    if (n <= 0 || n_hat <= 0 || n_hat > n || w <= 0) return -1;
+    lso_line *sv = malloc(n * sizeof(lso_line)), *ss = malloc(n * sizeof(lso_line));
+    char *in_v = calloc(n, 1), *in_s = calloc(n, 1);
+    int32_t *tmp = malloc((n + 1) * sizeof(int32_t));
+    if (!sv || !ss || !in_v || !in_s || !tmp) { free(sv); free(ss); free(in_v); free(in_s); free(tmp); return -2; }
+    for (int64_t i = 0; i < n; ++i) {
+        sv[i].w = vert[i];  sv[i].idx = (int32_t)i;
+        ss[i].w = slash[i]; ss[i].idx = (int32_t)i;
+    }
+    qsort(sv, n, sizeof(lso_line), lso_cmp_desc);
+    qsort(ss, n, sizeof(lso_line), lso_cmp_desc);
+    volatile float target = alpha * total;
+    float sum = 0.0f, prev = 0.0f;
+    int64_t is = 0, iv = 0;
+    while (sum < target && (is < n || iv < n)) {
+        volatile float ds = 0.0f, dv = 0.0f;
+        if (is < n) {                                   /* the slash at the head of its list */
+            const int64_t o = ss[is].idx;
+            double ov = 0.0;
+            for (int t = 0; t < w; ++t) {
+                const int64_t c = (q_pos ? q_pos[t] : n - w + t) - o;
+                if (c >= 0 && in_v[c]) ov += (double)a_win[(int64_t)t * n + c];
+            }
+            ds = ss[is].w - (float)ov;
+        }
+        if (iv < n) {                                   /* the column at the head of its list */
+            const int64_t b = sv[iv].idx;
+            double ov = 0.0;
+            for (int t = 0; t < w; ++t) {
+                const int64_t o = (q_pos ? q_pos[t] : n - w + t) - b;
+                if (o >= 0 && in_s[o]) ov += (double)a_win[(int64_t)t * n + b];
+            }
+            dv = sv[iv].w - (float)ov;
+        }
+        int take_s;
+        if (iv >= n) take_s = 1;
+        else if (is >= n) take_s = 0;
+        else {
+            const int64_t o = ss[is].idx, b = sv[iv].idx;
+            float cs = (float)((n - o) < n_hat ? (n - o) : n_hat) - (float)iv; if (cs < 1.0f) cs = 1.0f;
+            float cv = (float)((n - b) < n_hat ? (n - b) : n_hat) - (float)is; if (cv < 1.0f) cv = 1.0f;
+            volatile float lhs = ds * cv;
+            volatile float rhs = dv * cs;
+            take_s = (lhs >= rhs);
+        }
+        prev = sum;
+        if (take_s) { sum = sum + ds; in_s[ss[is].idx] = 1; ++is; }
+        else        { sum = sum + dv; in_v[sv[iv].idx] = 1; ++iv; }
+    }
+    for (int64_t i = 0; i < is; ++i) tmp[i] = ss[i].idx;
+    qsort(tmp, is, sizeof(int32_t), lso_cmp_i32);
+    for (int64_t i = 0; i < is && i < cap_s; ++i) s_idx[i] = tmp[i];
+    for (int64_t i = 0; i < iv; ++i) tmp[i] = sv[i].idx;
+    qsort(tmp, iv, sizeof(int32_t), lso_cmp_i32);
+    for (int64_t i = 0; i < iv && i < cap_v; ++i) v_idx[i] = tmp[i];
+    *s_cnt = (int32_t)is; *v_cnt = (int32_t)iv;
+    *accounted = sum; *before_last = prev;
+    free(sv); free(ss); free(in_v); free(in_s); free(tmp);
+    return 0;
+}
+
+/* lso_select_exact over all B*Hq heads; a_win is [B*Hq, w, n], the other arrays as in lso_select_all. */
+int lso_select_exact_all(int64_t heads, int64_t n, int64_t n_hat, int w, float alpha,
+                         const float *a_win, const int64_t *q_pos,
+                         const float *vert, const float *slash, const float *total,
+                         int32_t *v_idx, int32_t *v_cnt, int64_t cap_v,
+                         int32_t *s_idx, int32_t *s_cnt, int64_t cap_s,
+                         float *accounted, float *before_last)
+{
+    int rc = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t h = 0; h < heads; ++h) {
+        int r = lso_select_exact(n, n_hat, w, alpha, a_win + h * (int64_t)w * n, q_pos, vert + h * n, slash + h * n,
+                                 total[h], v_idx + h * cap_v, v_cnt + h, cap_v,
+                                 s_idx + h * cap_s, s_cnt + h, cap_s, accounted + h, before_last + h);
         if (r) rc = r;
     }
     return rc;

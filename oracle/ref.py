@@ -114,6 +114,43 @@ def select(sc, n_hat, alpha, cap_v=None, cap_s=None):
     return dict(v_idx=v_idx, v_cnt=v_cnt, s_idx=s_idx, s_cnt=s_cnt, accounted=acc, before_last=prev)
 
 
+def window(q_win, k, scale=None, q_pos=None):
+    """The window attention matrix of Alg. 2 (softmax step): a_win [B,Hq,w,n] float32, zero beyond each row's position."""
+    q_win, qp = _f(q_win); k, kp = _f(k)
+    B, Hq, w, d = q_win.shape
+    _, Hkv, n, _ = k.shape
+    scale = (1.0 / np.sqrt(d)) if scale is None else scale
+    a = np.zeros((B, Hq, w, n), np.float32)
+    pp = None
+    if q_pos is not None:
+        q_pos, pp = _i64(q_pos)
+    rc = lib().lso_window(B, Hq, Hkv, d, C.c_int64(n), w, C.c_double(scale), qp, pp, kp, _f(a)[1])
+    if rc:
+        raise RuntimeError(f"lso_window rc={rc}")
+    return a
+
+
+def select_exact(a_win, sc, n_hat, alpha, q_pos=None, cap_v=None, cap_s=None):
+    """Alg. 2 with the overlap of a candidate line counted cell by cell (lso_select_exact), every head.
+    a_win from window(), sc = dict from score() (vert, slash, total are used).  Same result dict as select()."""
+    a_win, ap = _f(a_win)
+    vert, vp = _f(sc["vert"]); slash, sp = _f(sc["slash"]); total, tp = _f(sc["total"])
+    B, Hq, w, n = a_win.shape
+    cap_v = int(cap_v or n); cap_s = int(cap_s or n)
+    v_idx = np.full((B, Hq, cap_v), -1, np.int32); s_idx = np.full((B, Hq, cap_s), -1, np.int32)
+    v_cnt = np.zeros((B, Hq), np.int32); s_cnt = np.zeros((B, Hq), np.int32)
+    acc = np.zeros((B, Hq), np.float32); prev = np.zeros((B, Hq), np.float32)
+    pp = None
+    if q_pos is not None:
+        q_pos, pp = _i64(q_pos)
+    rc = lib().lso_select_exact_all(C.c_int64(B * Hq), C.c_int64(n), C.c_int64(n_hat), w, C.c_float(alpha), ap, pp,
+                                    vp, sp, tp, _i32(v_idx)[1], _i32(v_cnt)[1], C.c_int64(cap_v),
+                                    _i32(s_idx)[1], _i32(s_cnt)[1], C.c_int64(cap_s), _f(acc)[1], _f(prev)[1])
+    if rc:
+        raise RuntimeError(f"lso_select_exact_all rc={rc}")
+    return dict(v_idx=v_idx, v_cnt=v_cnt, s_idx=s_idx, s_cnt=s_cnt, accounted=acc, before_last=prev)
+
+
 def attend(q, k, v, v_idx, v_cnt, s_idx, s_cnt, scale=None, rows=None, mode=1, want_lse=True):
     """Masked attention over selected lines for the rows of the newest turn.
     q [B,Hq,n_hat,d]; k, v [B,Hkv,n,d].  rows: flat ids ((b*Hq+h)*n_hat+a) or None = all.

@@ -498,3 +498,126 @@ def test_config_shapes_match_benchmark_definition():
     assert (c["stress_131k"].n, c["stress_131k"].n_hat, c["stress_131k"].w) == (131072, 16384, 128)
     assert (c["llama70b_16k_b4"].B, c["llama70b_16k_b4"].n_hat, c["llama70b_16k_b4"].Hq) == (4, 5462, 64)
     assert c["multiturn_32k"].causal_cells_per_head() == 298274361
+
+
+# ------------------------------------------------------------------ exact-overlap variant of Alg. 2
+
+def _line_sums_of(a_win, pos):
+    """vert / slash / total of window matrices a_win [B,Hq,w,n] (float64 sums -> float32)."""
+    B, Hq, w, n = a_win.shape
+    vert = a_win.astype(np.float64).sum(2)
+    slash = np.zeros((B, Hq, n))
+    for t in range(w):
+        for j in range(int(pos[t]) + 1):
+            slash[:, :, int(pos[t]) - j] += a_win[:, :, t, j]
+    return dict(vert=vert.astype(np.float32), slash=slash.astype(np.float32),
+                total=vert.sum(-1).astype(np.float32))
+
+
+def test_window_matrix_matches_bruteforce_and_line_sums(oracle):
+    B, Hq, Hkv, n, w, d = 1, 4, 2, 50, 7, 8
+    q, k, _ = inputs.make_plain(B, Hq, Hkv, n, w, d, seed=3, q_scale=3.0)
+    for pos in (None, np.array([3, 10, 11, 20, 33, 48, 49])):
+        a = oracle.window(q, k, q_pos=pos)
+        p = np.arange(n - w, n) if pos is None else pos
+        for h in range(Hq):
+            P = _dense_window_probs(q[0, h], k[0, h // (Hq // Hkv)], p, 1.0 / np.sqrt(d))
+            np.testing.assert_allclose(a[0, h], P, rtol=2e-6, atol=1e-12)
+        np.testing.assert_allclose(a.sum(-1), 1.0, rtol=1e-6)
+        sc = oracle.score(q, k, q_pos=pos)                      # the two oracle functions describe one matrix
+        ls = _line_sums_of(a, p)
+        np.testing.assert_allclose(ls["vert"], sc["vert"], rtol=1e-5, atol=1e-7)
+        np.testing.assert_allclose(ls["slash"], sc["slash"], rtol=1e-5, atol=1e-7)
+
+
+def test_exact_walk_worked_example(oracle):
+    rows, kv = [], {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "walk_exact_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *vals = line.split()
+        if key == "row":
+            rows.append([float(x) for x in vals])
+        else:
+            kv[key] = [float(x) for x in vals]
+    n, w, n_hat = int(kv["n"][0]), int(kv["w"][0]), int(kv["n_hat"][0])
+    a = np.array(rows, np.float32).reshape(1, 1, w, n)
+    sc = _line_sums_of(a, np.arange(n - w, n))
+    sel = oracle.select_exact(a, sc, n_hat, kv["alpha"][0])
+    assert list(sel["s_idx"][0, 0, :sel["s_cnt"][0, 0]]) == [int(x) for x in kv["expect_s"]]
+    assert list(sel["v_idx"][0, 0, :sel["v_cnt"][0, 0]]) == [int(x) for x in kv["expect_v"]]
+    assert sel["accounted"][0, 0] == np.float32(kv["expect_accounted"][0])
+    assert sel["before_last"][0, 0] == np.float32(kv["expect_before_last"][0])
+
+
+def _exact_walk_bruteforce(a, pos, vert, slash, total, n_hat, alpha):
+    """Alg. 2's loop where the gain of a line is, by definition, the weight of its cells that no selected line covers yet:
+    a boolean `covered` matrix is kept and re-read for every candidate (no overlap bookkeeping at all)."""
+    w, n = a.shape
+    f = np.float32
+    S = sorted(range(n), key=lambda i: (-slash[i], i)); V = sorted(range(n), key=lambda i: (-vert[i], i))
+    covered = np.zeros((w, n), bool)
+    cells_s = lambda o: [(t, int(pos[t]) - o) for t in range(w) if int(pos[t]) - o >= 0]
+    cells_v = lambda b: [(t, b) for t in range(w) if b <= int(pos[t])]
+    gain = lambda cells, wt: f(wt - f(sum(float(a[t, c]) for t, c in cells if covered[t, c])))
+    acc = f(0); tgt = f(alpha) * total
+    Ss, Vs = [], []
+    while acc < tgt and (S or V):
+        if not V:
+            pick = "s"
+        elif not S:
+            pick = "v"
+        else:
+            ds, dv = gain(cells_s(S[0]), slash[S[0]]), gain(cells_v(V[0]), vert[V[0]])
+            cs = max(f(1), f(min(n_hat, n - S[0])) - f(len(Vs))); cv = max(f(1), f(min(n_hat, n - V[0])) - f(len(Ss)))
+            pick = "s" if f(ds * cv) >= f(dv * cs) else "v"
+        if pick == "s":
+            s = S.pop(0); acc = f(acc + gain(cells_s(s), slash[s])); Ss.append(s)
+            for t, c in cells_s(s): covered[t, c] = True
+        else:
+            v = V.pop(0); acc = f(acc + gain(cells_v(v), vert[v])); Vs.append(v)
+            for t, c in cells_v(v): covered[t, c] = True
+    return sorted(Ss), sorted(Vs), acc, float(a.astype(np.float64)[covered].sum())
+
+
+@pytest.mark.parametrize("seed,pos_kind", [(1, "last"), (2, "last"), (3, "random")])
+def test_exact_walk_matches_bruteforce_union_coverage(oracle, seed, pos_kind):
+    """Sets and sum against the covered-matrix loop; the sum is the true weight of the union (up to binary32 rounding of the
+    running sum), gains are never negative, the walk stops at the first pick that reaches the target."""
+    n, n_hat, w, d = 72, 30, 9, 8
+    q, k, _ = inputs.make_plain(1, 2, 1, n, w, d, seed=seed, q_scale=4.0)
+    pos = np.arange(n - w, n) if pos_kind == "last" else np.sort(np.random.default_rng(seed).choice(np.arange(n - n_hat, n), w, replace=False))
+    qp = None if pos_kind == "last" else pos
+    a = oracle.window(q, k, q_pos=qp)
+    sc = oracle.score(q, k, q_pos=qp)
+    for alpha in (0.3, 0.8, 0.95, 1.0):
+        sel = oracle.select_exact(a, sc, n_hat, alpha, q_pos=qp)
+        for h in range(2):
+            Ss, Vs, acc, cov = _exact_walk_bruteforce(a[0, h], pos, sc["vert"][0, h], sc["slash"][0, h], sc["total"][0, h], n_hat, alpha)
+            assert Ss == list(sel["s_idx"][0, h, :sel["s_cnt"][0, h]])
+            assert Vs == list(sel["v_idx"][0, h, :sel["v_cnt"][0, h]])
+            assert acc == sel["accounted"][0, h]
+            np.testing.assert_allclose(sel["accounted"][0, h], cov, rtol=2e-5)
+            tgt = np.float32(alpha) * sc["total"][0, h]
+            exhausted = sel["s_cnt"][0, h] == n and sel["v_cnt"][0, h] == n
+            assert sel["before_last"][0, h] < tgt
+            assert exhausted or sel["accounted"][0, h] >= tgt
+            assert sel["before_last"][0, h] <= sel["accounted"][0, h]          # no pick ever lowers the sum
+
+
+def test_exact_walk_keeps_mixed_selections_where_the_bound_gives_up(oracle):
+    """On a structured workload the listing's bound drives some heads to take every line; with exact overlaps the same heads
+    stop at a mixed selection whose accounted weight reaches the target."""
+    cfg = inputs.scaled(inputs.CONFIGS["llama8b_8k"], n=1536, Hq=8, Hkv=2, heavy_lo=16, heavy_hi=48, span=128)
+    q, k, _, _ = inputs.make_inputs(cfg)
+    qw = q[:, :, -cfg.w:]
+    sc = oracle.score(qw, k)
+    a = oracle.window(qw, k)
+    bound = oracle.select(sc, cfg.n_hat, 0.95)
+    exact = oracle.select_exact(a, sc, cfg.n_hat, 0.95)
+    tgt = np.float32(0.95) * sc["total"]
+    assert np.all(exact["accounted"] >= tgt)
+    assert np.all((exact["s_cnt"] < cfg.n) | (exact["v_cnt"] < cfg.n))          # nobody takes everything
+    both = (exact["s_cnt"] > 0) & (exact["v_cnt"] > 0)
+    print("exact: mixed heads", int(both.sum()), "bound: exhausted heads", int(((bound["s_cnt"] == cfg.n) & (bound["v_cnt"] == cfg.n)).sum()))
+    assert both.any()
