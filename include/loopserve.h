@@ -118,6 +118,31 @@ int ls_select(ls_ctx* ctx, const ls_shape* shape, float alpha,
               float* accounted, void* hip_stream);
 
 /*
+ * ls_score_window / ls_select_exact -- Alg. 2 with the marginal contribution of a line taken exactly.
+ * Sec. 5.1 describes the quantities the loop compares as the marginal contributions of the two list
+ * heads; the listing bounds the part of a candidate that is already covered by the sum of w^max of the
+ * lines taken from the other list, which is what ls_select computes.  Here that part is added up cell by
+ * cell (a diagonal o and a column b share the cell of the scored row at position b + o, if there is one),
+ * so gains are never negative, the accounted sum is the weight of the union of the selected lines on the
+ * scored rows, and selections that mix columns and diagonals survive.  Opt-in: it needs the window
+ * matrix itself (w * n floats per head) and walks the lists one pick at a time.
+ *
+ * ls_score_window: the softmax step of Alg. 2 with the matrix kept.
+ *   q_win, q_pos, k as for ls_score;  a_win [B,Hq,w,n] fp32: A[t][b] for keys b <= p_t, 0 beyond.
+ * ls_select_exact: Desc_Sort and the loop.
+ *   a_win as above; q_pos [w] int64 device memory or NULL (the last w positions), the same as was scored;
+ *   vert, slash [B,Hq,n], total [B,Hq] as produced by ls_score (the lists are ordered by these weights);
+ *   outputs, capacities, accounted, status bits and limits as for ls_select (shape->w is used here).
+ */
+int ls_score_window(ls_ctx* ctx, const ls_shape* shape, const void* q_win, const int64_t* q_pos, const void* k,
+                    float* a_win, void* hip_stream);
+int ls_select_exact(ls_ctx* ctx, const ls_shape* shape, float alpha, const float* a_win, const int64_t* q_pos,
+                    const float* vert, const float* slash, const float* total,
+                    int32_t* v_idx, int32_t* v_cnt, int32_t cap_v,
+                    int32_t* s_idx, int32_t* s_cnt, int32_t cap_s,
+                    float* accounted, void* hip_stream);
+
+/*
  * ls_sparse_prefill -- masked attention Softmax(QK^T/sqrt(d_k) - c(1-M)) V of Sec. 2.2 for the
  * rows of the newest turn (Sec. 5, Step 1), with M[a][b] = 1 iff b <= p_a and (b in v_idx or
  * p_a - b in s_idx), masked entries weighing exactly zero, each allowed cell counted once.

@@ -57,6 +57,10 @@ def load_library():
     lib.ls_score.argtypes = [vp, sp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ls_select.restype = C.c_int
     lib.ls_select.argtypes = [vp, sp, f32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
+    lib.ls_score_window.restype = C.c_int
+    lib.ls_score_window.argtypes = [vp, sp, vp, vp, vp, vp, vp]
+    lib.ls_select_exact.restype = C.c_int
+    lib.ls_select_exact.argtypes = [vp, sp, f32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
     lib.ls_sparse_prefill.restype = C.c_int
     lib.ls_sparse_prefill.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.ls_kv_compress.restype = C.c_int
@@ -148,6 +152,14 @@ class Context:
         self._check(self.lib.ls_select(self.h, C.byref(shape), alpha, _ptr(vert), _ptr(slash), _ptr(vmax), _ptr(smax),
                                        _ptr(total), _ptr(v_idx), _ptr(v_cnt), v_idx.shape[-1], _ptr(s_idx),
                                        _ptr(s_cnt), s_idx.shape[-1], _ptr(accounted), _stream()))
+
+    def ls_score_window(self, shape, q_win, k, a_win, q_pos=None):
+        self._check(self.lib.ls_score_window(self.h, C.byref(shape), _ptr(q_win), _ptr(q_pos), _ptr(k), _ptr(a_win), _stream()))
+
+    def ls_select_exact(self, shape, alpha, a_win, vert, slash, total, v_idx, v_cnt, s_idx, s_cnt, accounted=None, q_pos=None):
+        self._check(self.lib.ls_select_exact(self.h, C.byref(shape), alpha, _ptr(a_win), _ptr(q_pos), _ptr(vert), _ptr(slash),
+                                             _ptr(total), _ptr(v_idx), _ptr(v_cnt), v_idx.shape[-1], _ptr(s_idx),
+                                             _ptr(s_cnt), s_idx.shape[-1], _ptr(accounted), _stream()))
 
     def ls_sparse_prefill(self, shape, q, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse=None):
         self._check(self.lib.ls_sparse_prefill(self.h, C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(v_idx),

@@ -216,6 +216,57 @@ int ls_score(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_p
     return LS_OK;
 }
 
+int ls_score_window(ls_ctx* c, const ls_shape* s, const void* q_win, const int64_t* q_pos, const void* k,
+                    float* a_win, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, false, true, false)) return fail(c, LS_ESHAPE, "ls_score_window: %s", m);
+    if (!q_win || !k || !a_win) return fail(c, LS_EINVAL, "ls_score_window: NULL tensor");
+    if (!aligned16(q_win) || !aligned16(k) || !aligned16(a_win) || (q_pos && (reinterpret_cast<uintptr_t>(q_pos) & 7u)))
+        return fail(c, LS_EINVAL, "ls_score_window: misaligned tensor");
+    ls::ScoreArgs a{};
+    a.q = q_win; a.k = k; a.q_pos = q_pos; a.n = s->n; a.w = s->w; a.G = s->Hq / s->Hkv; a.Hq = s->Hq;
+    a.Hkv = s->Hkv; a.B = s->B; a.BH = s->B * s->Hq; a.nkb = nkb_of(s->n); a.scale_log2e = scale_log2e(s);
+    Bump bp{c->ws, c->ws_bytes, 0};
+    a.part = bp.take<float>(part_floats(s));
+    a.rowstat = bp.take<float>((size_t)a.BH * a.w * 2);
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_score_window: workspace of %zu bytes is too small", c->ws_bytes);
+    a.a_win = a_win;
+    if (ls::score_lines_smem(s->w, s->dtype, s->d, 3) > 160 * 1024) return fail(c, LS_ESHAPE, "ls_score_window: w too large for LDS");
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_score_window: hipSetDevice failed");
+    const hipError_t e = ls::run_score(a, s->dtype, s->d, 3, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_score_window: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
+int ls_select_exact(ls_ctx* c, const ls_shape* s, float alpha, const float* a_win, const int64_t* q_pos,
+                    const float* vert, const float* slash, const float* total,
+                    int32_t* v_idx, int32_t* v_cnt, int32_t cap_v, int32_t* s_idx, int32_t* s_cnt, int32_t cap_s,
+                    float* accounted, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, true, true, true)) return fail(c, LS_ESHAPE, "ls_select_exact: %s", m);
+    if (!(alpha >= 0.f && alpha <= 1.f)) return fail(c, LS_EALPHA, "ls_select_exact: alpha %g outside [0, 1]", (double)alpha);
+    if (!a_win || !vert || !slash || !total || !v_idx || !v_cnt || !s_idx || !s_cnt)
+        return fail(c, LS_EINVAL, "ls_select_exact: NULL tensor");
+    if (q_pos && (reinterpret_cast<uintptr_t>(q_pos) & 7u)) return fail(c, LS_EINVAL, "ls_select_exact: misaligned q_pos");
+    if (cap_v <= 0 || cap_s <= 0) return fail(c, LS_ESHAPE, "ls_select_exact: capacities must be positive");
+    ls::SelectArgs a{};
+    a.n = s->n; a.n_hat = s->n_hat; a.BH = s->B * s->Hq; a.alpha = alpha;
+    a.vert = vert; a.slash = slash; a.vmax = vert; a.smax = slash; a.total = total;   // the maxima are not used: any readable array
+    Bump bp{c->ws, c->ws_bytes, 0};
+    const size_t cnt = 2 * (size_t)a.BH * (size_t)a.n;
+    a.skey0 = bp.take<uint32_t>(cnt);
+    a.sidx0 = bp.take<int32_t>(cnt); a.sidx1 = bp.take<int32_t>(cnt);
+    a.head_w = bp.take<float>(2 * (size_t)a.BH * ls::SELECT_HEAD_LINES); a.head_m = bp.take<float>(2 * (size_t)a.BH * ls::SELECT_HEAD_LINES);
+    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_select_exact: workspace of %zu bytes is too small", c->ws_bytes);
+    a.v_idx = v_idx; a.v_cnt = v_cnt; a.s_idx = s_idx; a.s_cnt = s_cnt; a.cap_v = cap_v; a.cap_s = cap_s;
+    a.accounted = accounted; a.status = c->status; a.spin_limit = c->walk_spin_limit;
+    a.a_win = a_win; a.q_pos = q_pos; a.w = s->w;
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_select_exact: hipSetDevice failed");
+    const hipError_t e = ls::run_select_exact(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_select_exact: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
 int ls_select(ls_ctx* c, const ls_shape* s, float alpha,
               const float* vert, const float* slash, const float* vmax, const float* smax, const float* total,
               int32_t* v_idx, int32_t* v_cnt, int32_t cap_v, int32_t* s_idx, int32_t* s_cnt, int32_t cap_s,

@@ -18,6 +18,7 @@ struct ScoreArgs {
     float* spart;             // [2][BH][n][2]    diagonal partial sum / max by key-block parity
     float *vert, *slash, *vmax, *smax, *total;
     float* gscore;            // [B*Hkv][n]       group-summed column sums (retention score)
+    float* a_win;             // [BH][w][n]       the window matrix itself (mode 3)
 };
 
 constexpr int SELECT_HEAD_LINES = 1024;   // lines at the front of each sorted list whose weight and maximum are stored in order
@@ -35,6 +36,10 @@ struct SelectArgs {
     float* accounted;         // may be null
     int32_t* status;          // device status word of the context (bits LS_STAT_*), OR-ed into
     int spin_limit;           // bound of every wait between the waves of walk_kernel
+    // exact-overlap variant (run_select_exact) only
+    const float* a_win;       // [BH][w][n] window matrix
+    const int64_t* q_pos;     // [w] positions of the scored rows, or null (the last w)
+    int w;
 };
 
 constexpr int64_t TOPB_MAX_LEN = 262144;   // longest score row run_topb takes
@@ -131,6 +136,7 @@ hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st);
 size_t decode_smem_bytes(int d, int G);
 size_t score_lines_smem(int w, int dtype, int d, int mode);
 hipError_t run_select(const SelectArgs& a, hipStream_t st);
+hipError_t run_select_exact(const SelectArgs& a, hipStream_t st);   // a_win, q_pos, w set; vmax / smax unused
 hipError_t run_topb(const TopbArgs& a, int BK, uint32_t* scratch, hipStream_t st);   // scratch: topb_scratch_words(BK, len) words
 size_t topb_scratch_words(int BK, int64_t len);
 hipError_t run_gather_rows(const void* src, void* dst, const int32_t* keep_idx, const int32_t* keep_cnt,

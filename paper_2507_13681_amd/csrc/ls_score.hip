@@ -209,6 +209,7 @@ __global__ __launch_bounds__(256) void merge_kernel(ScoreArgs a, int rows) {
 // MODE 0: vert/vmax per head + diagonal partials (contiguous window, q_pos == NULL)
 // MODE 1: vert/vmax per head + diagonals through atomics (explicit q_pos)
 // MODE 2: column sums only, summed over the G heads of the KV head (retention score)
+// MODE 3: no sums at all: the matrix A itself is written, [BH][w][n], zero beyond each row's position
 template <typename T, int D, int MODE>
 __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
     using QS = QStage<T, D>;
@@ -288,6 +289,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
                     ps += p;
                     pm = fmaxf(pm, p);
                     if (MODE == 0) slab[row * (SB + 1) + klocal] = p;
+                    if (MODE == 3 && row < a.w && mykey < n) a.a_win[((int64_t)bh * a.w + row) * n + mykey] = p;
                     if (MODE == 1 && p > 0.f) {
                         int64_t pr = a.q_pos ? a.q_pos[row] : n - a.w + row;
                         if (pr > n - 1) pr = n - 1;
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void lines_kernel(ScoreArgs a) {
             vmx = fmaxf(vmx, pm);
         }
         if (MODE == 2) gsum += vsum;
-        else if (g == 0 && mykey < n) {
+        else if (MODE != 3 && g == 0 && mykey < n) {
             a.vert[(int64_t)bh * n + mykey] = vsum;
             a.vmax[(int64_t)bh * n + mykey] = vmx;
         }
@@ -424,6 +426,9 @@ static hipError_t run_score_t(const ScoreArgs& a, int mode, hipStream_t st) {
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.slash, cnt);
         hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.smax, cnt);
         hipLaunchKernelGGL((lines_kernel<T, D, 1>), grid, dim3(SCORE_THREADS), smem, st, a);
+    } else if (mode == 3) {
+        hipLaunchKernelGGL((lines_kernel<T, D, 3>), grid, dim3(SCORE_THREADS), smem, st, a);
+        return hipGetLastError();
     } else {
         hipLaunchKernelGGL((lines_kernel<T, D, 2>), grid, dim3(SCORE_THREADS), smem, st, a);
         return hipGetLastError();
@@ -439,6 +444,7 @@ static hipError_t init_score_t() {
     if ((e = allow_full_lds(&stats_kernel<T, D>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&lines_kernel<T, D, 0>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&lines_kernel<T, D, 1>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&lines_kernel<T, D, 3>)) != hipSuccess) return e;
     return allow_full_lds(&lines_kernel<T, D, 2>);
 }
 hipError_t init_score_kernels() {

@@ -752,6 +752,195 @@ __global__ __launch_bounds__(WALK_THREADS) void walk_kernel(SelectArgs a) {
     }
 }
 
+// ---- Alg. 2 with the overlap of a candidate counted cell by cell ----------------------------------
+// The loop of Alg. 2 compares the marginal contributions of the two list heads (Sec. 5.1); the listing bounds the
+// part of a line that is already covered by the sum of w^max of the lines taken from the other list.  This variant
+// adds that part up exactly: a diagonal o and a column b share the cell of the scored row at position b + o, if
+// there is one, so
+//     overlap(slash o)  = sum over scored rows t with key c = p_t - o >= 0 and c taken  of A[t][c]
+//     overlap(column b) = sum over scored rows t with o = p_t - b >= 0 and o taken      of A[t][b]
+// "Taken" is a comparison of ranks: the lists are used up from the front, so column c is taken iff its position
+// in the sorted column list is below the number of columns taken so far.  A candidate therefore needs, once, the
+// w cells of its line and the ranks of the w lines it crosses; its overlap at any later moment is a masked sum of
+// those cells.  Everything else is the loop of walk_kernel (binary32, single roundings, cross-multiplied test).
+//
+// rank_kernel: inverse of the sorted order, rank[list][bh][line] = position of the line in its sorted list.
+__global__ void rank_kernel(SelectArgs a) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t seg = ((int64_t)blockIdx.z * a.BH + blockIdx.y) * a.n;
+    if (i < a.n) a.sidx0[seg + a.sidx1[seg + i]] = (int32_t)i;
+}
+
+constexpr int XW_THREADS = 192;                // wave 0 walks, waves 1 / 2 stage the records of the slash / column list
+constexpr int XW_CELLS = 2048;                 // cells of staged records per list: a ring of XW_CELLS / wpad records
+constexpr int XW_BATCH = 8;                    // records a stager fetches per round trip
+struct XwSync { int staged[2], head[2], done, err; };
+
+__device__ __forceinline__ double wave_sum_f64(double x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// grid (BH).  LDS: per list a ring of records (wpad cells + wpad ranks each) and per-record line index / weight.
+__global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
+    extern __shared__ __align__(16) unsigned char xw_lds[];
+    const int W = a.w, wpad = (W + 63) / 64 * 64, CP = wpad / 64, ring = XW_CELLS / wpad;      // ring >= 8 (w <= 256)
+    float* cells = reinterpret_cast<float*>(xw_lds);                       // [2][ring][wpad]
+    int32_t* ranks = reinterpret_cast<int32_t*>(cells + 2 * XW_CELLS);     // [2][ring][wpad]
+    int32_t* ridx = ranks + 2 * XW_CELLS;                                  // [2][ring] line index of a record
+    float* rwt = reinterpret_cast<float*>(ridx + 2 * 256);                 // [2][ring] its weight
+    XwSync* sync = reinterpret_cast<XwSync*>(rwt + 2 * 256);
+    const int bh = blockIdx.x, lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = (int)a.n;
+    const int spin_limit = a.spin_limit;
+    if (threadIdx.x == 0) { sync->staged[0] = sync->staged[1] = 0; sync->head[0] = sync->head[1] = 0; sync->done = 0; sync->err = 0; }
+    __syncthreads();
+
+    if (wv != 0) {
+        // ------------------------------------------------------------------ staging of one list
+        const int l = wv - 1;                                              // 0: slashes, 1: columns
+        const int32_t* sorted = a.sidx1 + ((int64_t)l * a.BH + bh) * a.n;
+        const int32_t* rank_other = a.sidx0 + ((int64_t)(1 - l) * a.BH + bh) * a.n;
+        const float* wts = (l == 0 ? a.slash : a.vert) + (int64_t)bh * a.n;
+        const float* A = a.a_win + (int64_t)bh * W * a.n;
+        int pos[4];                                                        // positions of this lane's rows t = lane + 64 c
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int t = lane + 64 * c;
+            int64_t p = t < W ? (a.q_pos ? a.q_pos[t] : (int64_t)n - W + t) : -1;
+            if (p > n - 1) p = n - 1;
+            pos[c] = (int)p;
+        }
+        int j = 0, spins = 0;
+        while (j < n && walk_ld(&sync->done) == 0) {
+            const int room = walk_ld(&sync->head[l]) + ring - j;           // records that may be written
+            if (room <= 0) {
+                __builtin_amdgcn_s_sleep(2);
+                if (++spins > spin_limit) { walk_st(&sync->err, 1); break; }
+                continue;
+            }
+            spins = 0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            int batch = room < XW_BATCH ? room : XW_BATCH;
+            if (batch > n - j) batch = n - j;
+            int32_t idx[XW_BATCH];
+#pragma unroll
+            for (int r = 0; r < XW_BATCH; ++r) idx[r] = sorted[j + (r < batch ? r : 0)];
+            float wt[XW_BATCH], cell[XW_BATCH][4];
+            int32_t rk[XW_BATCH][4];
+#pragma unroll
+            for (int r = 0; r < XW_BATCH; ++r) {
+                wt[r] = wts[idx[r]];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    cell[r][c] = 0.f; rk[r][c] = 0x7FFFFFFF;
+                    if (c < CP) {
+                        const int t = lane + 64 * c;
+                        const int other = pos[c] - idx[r];                 // the crossed line of the other kind (key, or diagonal)
+                        if (t < W && other >= 0) {
+                            const int key = l == 0 ? other : idx[r];
+                            cell[r][c] = A[(int64_t)t * a.n + key];
+                            rk[r][c] = rank_other[other];
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < XW_BATCH; ++r) {
+                if (r < batch) {
+                    const int slot = (j + r) % ring;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (c < CP) {
+                            cells[(l * ring + slot) * wpad + lane + 64 * c] = cell[r][c];
+                            ranks[(l * ring + slot) * wpad + lane + 64 * c] = rk[r][c];
+                        }
+                    if (lane == 0) { ridx[l * 256 + slot] = idx[r]; rwt[l * 256 + slot] = wt[r]; }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            j += batch;
+            if (lane == 0) walk_st(&sync->staged[l], j);
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- the walk (wave 0)
+    const float target = a.alpha * a.total[bh];
+    const float nh = (float)a.n_hat;
+    float sum = 0.f;
+    int is = 0, iv = 0;
+    bool failed = false;
+    // head record of each list, read again only when that head moves
+    float c_s[4], c_v[4], w_s = 0.f, w_v = 0.f, l_s = 1.f, l_v = 1.f;
+    int32_t r_s[4], r_v[4];
+    auto wait_record = [&](int l, int want) {              // until record `want` of list l is staged
+        int spins = 0;
+        while (walk_ld(&sync->staged[l]) <= want) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > spin_limit || walk_ld(&sync->err)) { failed = true; break; }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    };
+    auto read_record = [&](int l, int h, float (&c)[4], int32_t (&r)[4], float& wt, float& len) {
+        const int slot = h % ring;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            c[q] = 0.f; r[q] = 0x7FFFFFFF;
+            if (q < CP) { c[q] = cells[(l * ring + slot) * wpad + lane + 64 * q]; r[q] = ranks[(l * ring + slot) * wpad + lane + 64 * q]; }
+        }
+        const int line = ridx[l * 256 + slot];
+        wt = rwt[l * 256 + slot];
+        const float rest = (float)(n - line);
+        len = rest < nh ? rest : nh;
+    };
+    auto overlap = [&](const float (&c)[4], const int32_t (&r)[4], int taken_other) -> float {
+        double x = 0.0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x += r[q] < taken_other ? (double)c[q] : 0.0;
+        return (float)wave_sum_f64(x);
+    };
+    if (n > 0) { wait_record(0, 0); wait_record(1, 0); }
+    if (!failed) { read_record(0, 0, c_s, r_s, w_s, l_s); read_record(1, 0, c_v, r_v, w_v, l_v); }
+    while (!failed && sum < target && (is < n || iv < n)) {
+        const bool has_s = is < n, has_v = iv < n;
+        const float ds = has_s ? __fsub_rn(w_s, overlap(c_s, r_s, iv)) : 0.f;
+        const float dv = has_v ? __fsub_rn(w_v, overlap(c_v, r_v, is)) : 0.f;
+        bool take_s;
+        if (!has_v) take_s = true;
+        else if (!has_s) take_s = false;
+        else {
+            float cs = __fsub_rn(l_s, (float)iv); if (cs < 1.0f) cs = 1.0f;
+            float cv = __fsub_rn(l_v, (float)is); if (cv < 1.0f) cv = 1.0f;
+            take_s = __fmul_rn(ds, cv) >= __fmul_rn(dv, cs);
+        }
+        if (take_s) {
+            sum = __fadd_rn(sum, ds);
+            ++is;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the record left behind
+            if (lane == 0) walk_st(&sync->head[0], is);
+            if (is < n && !(sum >= target)) { wait_record(0, is); if (!failed) read_record(0, is, c_s, r_s, w_s, l_s); }
+        } else {
+            sum = __fadd_rn(sum, dv);
+            ++iv;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (lane == 0) walk_st(&sync->head[1], iv);
+            if (iv < n && !(sum >= target)) { wait_record(1, iv); if (!failed) read_record(1, iv, c_v, r_v, w_v, l_v); }
+        }
+    }
+    if (lane == 0) {
+        if (failed) { walk_st(&sync->err, 1); atomicOr(a.status, STAT_WALK_TIMEOUT); }
+        walk_st(&sync->done, 1);
+        // a wait that ran into its bound reports every line selected (the coverage target still holds)
+        a.s_cnt[bh] = failed ? n : is;
+        a.v_cnt[bh] = failed ? n : iv;
+        if (a.accounted) a.accounted[bh] = sum;
+    }
+}
+
 // ---- chosen prefix -> ascending index list --------------------------------------------------------
 // grid (2, BH); dynamic LDS: bitmap of n bits + per-wave word counts.
 __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
@@ -1022,6 +1211,7 @@ hipError_t init_select_kernels() {
     if ((e = allow_full_lds(&sort_merge_kernel<4096>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&sort_merge_kernel<SORT_SEG_MAX>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&walk_kernel)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&walk_exact_kernel)) != hipSuccess) return e;
     return allow_full_lds(&emit_kernel);
 }
 
@@ -1034,6 +1224,20 @@ hipError_t run_select(const SelectArgs& a, hipStream_t st) {
                                         : launch_sort<SORT_SEG_MAX>(a, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(walk_kernel, dim3(a.BH), dim3(WALK_THREADS), WALK_LDS_BYTES, st, a);
+    const size_t smem = (size_t)((a.n + 31) / 32) * 4;
+    hipLaunchKernelGGL(emit_kernel, dim3(2, a.BH), dim3(1024), smem, st, a);
+    return hipGetLastError();
+}
+
+hipError_t run_select_exact(const SelectArgs& a, hipStream_t st) {
+    const int64_t want = a.n * 2 * a.BH / 256;
+    hipError_t e = want <= SORT_SEG_MIN ? launch_sort<SORT_SEG_MIN>(a, st)
+                 : want <= 4096         ? launch_sort<4096>(a, st)
+                                        : launch_sort<SORT_SEG_MAX>(a, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((a.n + 255) / 256), a.BH, 2), dim3(256), 0, st, a);
+    const size_t xw = 2 * XW_CELLS * 8 + 2 * 256 * 8 + sizeof(XwSync) + 16;
+    hipLaunchKernelGGL(walk_exact_kernel, dim3(a.BH), dim3(XW_THREADS), xw, st, a);
     const size_t smem = (size_t)((a.n + 31) / 32) * 4;
     hipLaunchKernelGGL(emit_kernel, dim3(2, a.BH), dim3(1024), smem, st, a);
     return hipGetLastError();
