@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--budget", type=int, default=2048)
     ap.add_argument("--n-obs", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--exact-overlap", action="store_true",
+                    help="select with ls_score_window + ls_select_exact (overlaps counted cell by cell) instead of ls_select; "
+                         "not the headline configuration")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel, measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
                          "this same command (see profiles/); counters cannot be read inside a timed run, so roofline.traffic is "
@@ -133,7 +136,14 @@ def main():
     def f_score():
         ctx.ls_score(shape, qwin, kd, sc["vert"], sc["slash"], sc["vmax"], sc["smax"], sc["total"])
 
+    a_win = torch.empty((cfg.B, cfg.Hq, cfg.w, cfg.n), dtype=torch.float32, device="cuda") if args.exact_overlap else None
+
     def f_select():
+        if args.exact_overlap:
+            ctx.ls_score_window(shape, qwin, kd, a_win)
+            ctx.ls_select_exact(shape, alpha, a_win, sc["vert"], sc["slash"], sc["total"],
+                                sel["v_idx"], sel["v_cnt"], sel["s_idx"], sel["s_cnt"], None)
+            return
         ctx.ls_select(shape, alpha, sc["vert"], sc["slash"], sc["vmax"], sc["smax"], sc["total"],
                       sel["v_idx"], sel["v_cnt"], sel["s_idx"], sel["s_cnt"], None)
 
@@ -185,7 +195,9 @@ def main():
 
     # What each kind of head costs the attention kernel (outside the timed region): the launch is repeated with the
     # lists of one kind emptied, and the kind is charged the time the full launch takes longer than that one.
-    def kernel_ms_with(v_cnt, s_cnt, reps=3):
+    def kernel_ms_with(v_cnt, s_cnt, reps=5):
+        ctx.ls_sparse_prefill(shape, qd, kd, vd, sel["v_idx"], v_cnt, sel["s_idx"], s_cnt, out, lse)     # untimed
+        torch.cuda.synchronize()
         ctx.profile_enable(True)
         for _ in range(reps):
             ctx.ls_sparse_prefill(shape, qd, kd, vd, sel["v_idx"], v_cnt, sel["s_idx"], s_cnt, out, lse)
@@ -222,7 +234,7 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "B": cfg.B, "n": cfg.n, "n_hat": cfg.n_hat, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
+        "config": {"workload": cfg.name, "selection": "exact overlap" if args.exact_overlap else "Alg. 2 bound", "B": cfg.B, "n": cfg.n, "n_hat": cfg.n_hat, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
                    "d": cfg.d, "w": cfg.w, "alpha": alpha, "kv_budget": args.budget, "n_obs": args.n_obs,
                    "parallelism": "single GPU"},
         "pct_of_peak": round(100.0 * value / peak, 2),
