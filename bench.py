@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--budget", type=int, default=2048)
     ap.add_argument("--n-obs", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--compress-gather", action="store_true",
+                    help="ls_kv_compress also writes the compacted K / V copies of the kept rows (adds its row-gather kernel to the step)")
     ap.add_argument("--exact-overlap", action="store_true",
                     help="select with ls_score_window + ls_select_exact (overlaps counted cell by cell) instead of ls_select; "
                          "not the headline configuration")
@@ -150,8 +152,13 @@ def main():
     def f_prefill():
         ctx.ls_sparse_prefill(shape, qd, kd, vd, sel["v_idx"], sel["v_cnt"], sel["s_idx"], sel["s_cnt"], out, lse)
 
+    k_keep = v_keep = None
+    if args.compress_gather:
+        k_keep = torch.empty((cfg.B, cfg.Hkv, args.budget, cfg.d), dtype=tdt, device="cuda")
+        v_keep = torch.empty_like(k_keep)
+
     def f_compress():
-        cctx.ls_kv_compress(cshape, args.budget, qobs, kd, None, keep_idx, keep_cnt)
+        cctx.ls_kv_compress(cshape, args.budget, qobs, kd, vd if args.compress_gather else None, keep_idx, keep_cnt, k_keep, v_keep)
 
     def step():
         # compress is issued once the scoring kernels (which fill the chip themselves) are queued, so that it runs
