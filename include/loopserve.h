@@ -143,6 +143,26 @@ int ls_select_exact(ls_ctx* ctx, const ls_shape* shape, float alpha, const float
                     float* accounted, void* hip_stream);
 
 /*
+ * ls_merge_lines -- the accumulated line set of Alg. 1 (L: the selections of every turn so far), which Sec. 5,
+ * Step 1 says can be reused in later dialogue turns.  A column index is a key position and a diagonal index an
+ * offset (query position - key position); neither changes when the context grows, so a selection made in an
+ * earlier turn is carried into a later one as a union of index sets.  Per (batch, head): v_idx = union of the
+ * column lists a and b, s_idx = union of the diagonal lists, each ascending and free of duplicates, with their
+ * counts (a count above its capacity: truncated to the smallest indices, LS_STAT_S_TRUNCATED / V_TRUNCATED).
+ *   shape: B, Hq and n (the context the result refers to) are used; entries outside [0, n) are dropped
+ *          (LS_STAT_MERGE_RANGE).  min(cnt, cap) entries of each input list are read; inputs need not be sorted.
+ *   The output lists are valid inputs of ls_sparse_prefill and of a later ls_merge_lines; an output may not
+ *   alias an input.
+ */
+int ls_merge_lines(ls_ctx* ctx, const ls_shape* shape,
+                   const int32_t* v_idx_a, const int32_t* v_cnt_a, int32_t cap_va,
+                   const int32_t* s_idx_a, const int32_t* s_cnt_a, int32_t cap_sa,
+                   const int32_t* v_idx_b, const int32_t* v_cnt_b, int32_t cap_vb,
+                   const int32_t* s_idx_b, const int32_t* s_cnt_b, int32_t cap_sb,
+                   int32_t* v_idx, int32_t* v_cnt, int32_t cap_v,
+                   int32_t* s_idx, int32_t* s_cnt, int32_t cap_s, void* hip_stream);
+
+/*
  * ls_sparse_prefill -- masked attention Softmax(QK^T/sqrt(d_k) - c(1-M)) V of Sec. 2.2 for the
  * rows of the newest turn (Sec. 5, Step 1), with M[a][b] = 1 iff b <= p_a and (b in v_idx or
  * p_a - b in s_idx), masked entries weighing exactly zero, each allowed cell counted once.
@@ -248,6 +268,7 @@ int ls_profile_prefill_kernel_ms(ls_ctx* ctx, double* mean_ms, int32_t* launches
 #define LS_STAT_S_RANGE      8  /* ls_sparse_prefill: s_idx entries outside [0, n) were ignored */
 #define LS_STAT_V_INVALID   16  /* ls_sparse_prefill: a head's v_idx was not strictly ascending inside [0, n); that
                                    head's columns were ignored (its diagonals still apply) */
+#define LS_STAT_MERGE_RANGE 32  /* ls_merge_lines: input entries outside [0, n) were dropped */
 int ls_poll_status(ls_ctx* ctx, int32_t* host_out, void* hip_stream);
 
 #ifdef __cplusplus

@@ -23,6 +23,7 @@ ENTRY_POINTS = ("ls_workspace_bytes", "ls_create", "ls_destroy", "ls_last_error"
                 "ls_score", "ls_select", "ls_sparse_prefill", "ls_kv_compress", "ls_poll_status")
 # bits of the device status word (ls_poll_status)
 LS_STAT_WALK_TIMEOUT, LS_STAT_S_TRUNCATED, LS_STAT_V_TRUNCATED, LS_STAT_S_RANGE, LS_STAT_V_INVALID = 1, 2, 4, 8, 16
+LS_STAT_MERGE_RANGE = 32
 
 
 class LsShape(C.Structure):
@@ -61,6 +62,8 @@ def load_library():
     lib.ls_score_window.argtypes = [vp, sp, vp, vp, vp, vp, vp]
     lib.ls_select_exact.restype = C.c_int
     lib.ls_select_exact.argtypes = [vp, sp, f32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
+    lib.ls_merge_lines.restype = C.c_int
+    lib.ls_merge_lines.argtypes = [vp, sp] + [vp, vp, i32] * 6 + [vp]
     lib.ls_sparse_prefill.restype = C.c_int
     lib.ls_sparse_prefill.argtypes = [vp, sp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     lib.ls_kv_compress.restype = C.c_int
@@ -160,6 +163,13 @@ class Context:
         self._check(self.lib.ls_select_exact(self.h, C.byref(shape), alpha, _ptr(a_win), _ptr(q_pos), _ptr(vert), _ptr(slash),
                                              _ptr(total), _ptr(v_idx), _ptr(v_cnt), v_idx.shape[-1], _ptr(s_idx),
                                              _ptr(s_cnt), s_idx.shape[-1], _ptr(accounted), _stream()))
+
+    def ls_merge_lines(self, shape, a, b, out):
+        """a, b, out: dicts with v_idx, v_cnt, s_idx, s_cnt (as alloc_select returns them)."""
+        args = []
+        for d in (a, b, out):
+            args += [_ptr(d["v_idx"]), _ptr(d["v_cnt"]), d["v_idx"].shape[-1], _ptr(d["s_idx"]), _ptr(d["s_cnt"]), d["s_idx"].shape[-1]]
+        self._check(self.lib.ls_merge_lines(self.h, C.byref(shape), *args, _stream()))
 
     def ls_sparse_prefill(self, shape, q, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse=None):
         self._check(self.lib.ls_sparse_prefill(self.h, C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(v_idx),

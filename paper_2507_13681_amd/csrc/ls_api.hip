@@ -17,7 +17,8 @@
 static_assert(ls::TOPB_MAX_LEN == LS_MAX_N, "ls_kv_compress documents LS_MAX_N as its longest cache");
 static_assert(ls::STAT_WALK_TIMEOUT == LS_STAT_WALK_TIMEOUT && ls::STAT_S_TRUNCATED == LS_STAT_S_TRUNCATED &&
               ls::STAT_V_TRUNCATED == LS_STAT_V_TRUNCATED && ls::STAT_S_RANGE == LS_STAT_S_RANGE &&
-              ls::STAT_V_INVALID == LS_STAT_V_INVALID, "status bits of the kernels and of the header");
+              ls::STAT_V_INVALID == LS_STAT_V_INVALID && ls::STAT_MERGE_RANGE == LS_STAT_MERGE_RANGE,
+              "status bits of the kernels and of the header");
 
 struct ls_ctx {
     int device;
@@ -291,6 +292,29 @@ int ls_select(ls_ctx* c, const ls_shape* s, float alpha,
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_select: hipSetDevice failed");
     const hipError_t e = ls::run_select(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(c, LS_EHIP, "ls_select: %s", hipGetErrorString(e));
+    return LS_OK;
+}
+
+int ls_merge_lines(ls_ctx* c, const ls_shape* s,
+                   const int32_t* v_idx_a, const int32_t* v_cnt_a, int32_t cap_va,
+                   const int32_t* s_idx_a, const int32_t* s_cnt_a, int32_t cap_sa,
+                   const int32_t* v_idx_b, const int32_t* v_cnt_b, int32_t cap_vb,
+                   const int32_t* s_idx_b, const int32_t* s_cnt_b, int32_t cap_sb,
+                   int32_t* v_idx, int32_t* v_cnt, int32_t cap_v, int32_t* s_idx, int32_t* s_cnt, int32_t cap_s, void* stream) {
+    if (!c) return LS_EINVAL;
+    if (const char* m = check_shape(s, false, false, true)) return fail(c, LS_ESHAPE, "ls_merge_lines: %s", m);
+    if (!v_idx_a || !v_cnt_a || !s_idx_a || !s_cnt_a || !v_idx_b || !v_cnt_b || !s_idx_b || !s_cnt_b || !v_idx || !v_cnt || !s_idx || !s_cnt)
+        return fail(c, LS_EINVAL, "ls_merge_lines: NULL tensor");
+    if (cap_va <= 0 || cap_sa <= 0 || cap_vb <= 0 || cap_sb <= 0 || cap_v <= 0 || cap_s <= 0)
+        return fail(c, LS_ESHAPE, "ls_merge_lines: capacities must be positive");
+    ls::MergeArgs a{};
+    a.n = s->n; a.BH = s->B * s->Hq; a.status = c->status;
+    a.idx_a[0] = s_idx_a; a.cnt_a[0] = s_cnt_a; a.cap_a[0] = cap_sa; a.idx_a[1] = v_idx_a; a.cnt_a[1] = v_cnt_a; a.cap_a[1] = cap_va;
+    a.idx_b[0] = s_idx_b; a.cnt_b[0] = s_cnt_b; a.cap_b[0] = cap_sb; a.idx_b[1] = v_idx_b; a.cnt_b[1] = v_cnt_b; a.cap_b[1] = cap_vb;
+    a.idx[0] = s_idx; a.cnt[0] = s_cnt; a.cap[0] = cap_s; a.idx[1] = v_idx; a.cnt[1] = v_cnt; a.cap[1] = cap_v;
+    if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_merge_lines: hipSetDevice failed");
+    const hipError_t e = ls::run_merge_lines(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(c, LS_EHIP, "ls_merge_lines: %s", hipGetErrorString(e));
     return LS_OK;
 }
 

@@ -111,7 +111,8 @@ struct DecodeArgs {
 };
 
 // status bits (mirrors of LS_STAT_* in loopserve.h)
-constexpr int STAT_WALK_TIMEOUT = 1, STAT_S_TRUNCATED = 2, STAT_V_TRUNCATED = 4, STAT_S_RANGE = 8, STAT_V_INVALID = 16;
+constexpr int STAT_WALK_TIMEOUT = 1, STAT_S_TRUNCATED = 2, STAT_V_TRUNCATED = 4, STAT_S_RANGE = 8, STAT_V_INVALID = 16,
+              STAT_MERGE_RANGE = 32;
 constexpr int WALK_SPIN_DEFAULT = 1 << 22;   // never reached in practice (about a second of polling)
 
 // Lets a kernel use all of a compute unit's LDS (160 KB, less what the kernel declares statically) as
@@ -135,6 +136,17 @@ hipError_t run_score(const ScoreArgs& a, int dtype, int d, int mode, hipStream_t
 hipError_t run_decode(const DecodeArgs& a, int d, hipStream_t st);
 size_t decode_smem_bytes(int d, int G);
 size_t score_lines_smem(int w, int dtype, int d, int mode);
+// Union of two selections per head (the accumulated line set of Alg. 1): lists a and b in, ascending unique list out.
+struct MergeArgs {
+    int64_t n;
+    int BH;
+    const int32_t *idx_a[2], *cnt_a[2], *idx_b[2], *cnt_b[2];   // [0] diagonals, [1] columns
+    int cap_a[2], cap_b[2];
+    int32_t *idx[2], *cnt[2];
+    int cap[2];
+    int32_t* status;
+};
+hipError_t run_merge_lines(const MergeArgs& a, hipStream_t st);
 hipError_t run_select(const SelectArgs& a, hipStream_t st);
 hipError_t run_select_exact(const SelectArgs& a, hipStream_t st);   // a_win, q_pos, w set; vmax / smax unused
 hipError_t run_topb(const TopbArgs& a, int BK, uint32_t* scratch, hipStream_t st);   // scratch: topb_scratch_words(BK, len) words

@@ -996,6 +996,73 @@ __global__ __launch_bounds__(1024) void emit_kernel(SelectArgs a) {
     }
 }
 
+// ---- union of two selections ------------------------------------------------------------------------
+// Alg. 1 keeps the lines selected in every turn so far (its set L); Sec. 5, Step 1 notes that selected lines can be
+// reused in later turns.  Column indices are key positions and diagonal indices are offsets, both unchanged when the
+// context grows, so carrying a selection into a later turn is a union of index sets.  grid (2, BH): list 0 =
+// diagonals, list 1 = columns; both inputs are marked in an LDS bitmap of n bits, which is then written out in order.
+__global__ __launch_bounds__(1024) void merge_lines_kernel(MergeArgs a) {
+    extern __shared__ uint32_t bm[];
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t carry;
+    const int list = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int64_t n = a.n;
+    const int words = (int)((n + 31) / 32);
+    for (int i = tid; i < words; i += 1024) bm[i] = 0u;
+    if (tid == 0) carry = 0u;
+    __syncthreads();
+    bool dropped = false;
+    for (int src = 0; src < 2; ++src) {
+        const int32_t* idx = (src ? a.idx_b[list] : a.idx_a[list]) + (int64_t)bh * (src ? a.cap_b[list] : a.cap_a[list]);
+        int cnt = (src ? a.cnt_b[list] : a.cnt_a[list])[bh];
+        const int cap = src ? a.cap_b[list] : a.cap_a[list];
+        if (cnt > cap) cnt = cap;
+        for (int i = tid; i < cnt; i += 1024) {
+            const int32_t x = idx[i];
+            if (x >= 0 && x < n) atomicOr(&bm[x >> 5], 1u << (x & 31)); else dropped = true;
+        }
+    }
+    dropped = __syncthreads_or(dropped);
+    int32_t* out = a.idx[list] + (int64_t)bh * a.cap[list];
+    const int cap = a.cap[list];
+    uint32_t total = 0;
+    for (int w0 = 0; w0 < words; w0 += 1024) {
+        const int wd = w0 + tid;
+        const uint32_t m = wd < words ? bm[wd] : 0u;
+        const uint32_t c = __popc(m);
+        uint32_t inc = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) { const uint32_t t = __shfl_up(inc, off, 64); if (lane >= off) inc += t; }
+        if (lane == 63) wsum[wv] = inc;
+        __syncthreads();
+        uint32_t pre = carry;
+        for (int w = 0; w < wv; ++w) pre += wsum[w];
+        uint32_t pos = pre + inc - c;
+        uint32_t mm = m;
+        while (mm) {
+            const int bit = __ffs(mm) - 1;
+            mm &= mm - 1;
+            if (pos < (uint32_t)cap) out[pos] = wd * 32 + bit;
+            ++pos;
+        }
+        __syncthreads();
+        if (tid == 1023) { carry = pre + inc; }
+        __syncthreads();
+        total = carry;
+    }
+    if (tid == 0) {
+        a.cnt[list][bh] = (int32_t)total;
+        if (total > (uint32_t)cap) atomicOr(a.status, list == 0 ? STAT_S_TRUNCATED : STAT_V_TRUNCATED);
+        if (dropped) atomicOr(a.status, STAT_MERGE_RANGE);
+    }
+}
+
+hipError_t run_merge_lines(const MergeArgs& a, hipStream_t st) {
+    const size_t smem = (size_t)((a.n + 31) / 32) * 4;
+    hipLaunchKernelGGL(merge_lines_kernel, dim3(2, a.BH), dim3(1024), smem, st, a);
+    return hipGetLastError();
+}
+
 // ---- top-B retention ------------------------------------------------------------------------------
 // keep_idx [BK][budget] ascending; keep_cnt = min(budget, len).
 // Radix select on the descending keys in three digits (11 + 11 + 10 bits, most significant first) finds the
@@ -1212,6 +1279,7 @@ hipError_t init_select_kernels() {
     if ((e = allow_full_lds(&sort_merge_kernel<SORT_SEG_MAX>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&walk_kernel)) != hipSuccess) return e;
     if ((e = allow_full_lds(&walk_exact_kernel)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&merge_lines_kernel)) != hipSuccess) return e;
     return allow_full_lds(&emit_kernel);
 }
 

@@ -34,6 +34,30 @@ def selection_cells(n: int, n_hat: int, sel: dict) -> np.ndarray:
     return out
 
 
+def visited_tiles(n: int, n_hat: int, v_idx, s_idx, rows: int = 128, keys: int = 64) -> int:
+    """Number of (rows x keys) tiles the sparse attention kernel visits for one head: per block of `rows` query rows
+    (aligned to absolute positions that are multiples of `rows`), the key blocks of `keys` keys that hold a cell on a
+    selected diagonal, plus the packed tiles of `keys` gathered columns each (none when every diagonal is selected).
+    Reports split the kernel's time between heads in proportion to this count."""
+    v = np.unique(np.asarray(v_idx, dtype=np.int64))
+    s = np.unique(np.asarray(s_idx, dtype=np.int64))
+    bm = np.zeros(n + 1, np.int64)
+    bm[s[(s >= 0) & (s < n)]] = 1
+    cs = np.concatenate(([0], np.cumsum(bm[:n])))           # cs[i] = selected diagonals below i
+    pos0 = (n - n_hat) // rows * rows
+    every = len(s) >= n
+    tiles = 0
+    for bp in range(pos0, n, rows):
+        posmax = min(bp + rows - 1, n - 1)
+        kb = np.arange(posmax // keys + 1)
+        lo = np.clip(bp - (kb * keys + keys - 1), 0, n)      # diagonals of the tile: (first row - last key) .. (last row - first key)
+        hi = np.clip(bp + rows - 1 - kb * keys + 1, 0, n)
+        tiles += int(((cs[np.maximum(hi, lo)] - cs[lo]) > 0).sum())
+        if not every:
+            tiles += -(-int(np.searchsorted(v, posmax, side="right")) // keys)
+    return tiles
+
+
 def causal_cells(n: int, n_hat: int) -> int:
     return n_hat * (n - n_hat) + n_hat * (n_hat + 1) // 2
 

@@ -46,3 +46,26 @@ def test_coverage_from_lse_matches_bruteforce(oracle):
             keep = np.array([(b in vs) or ((p - b) in ss) for b in range(p + 1)])
             np.testing.assert_allclose(cov[0, h, a], w[keep].sum(), rtol=1e-5)
     assert np.all(metrics.coverage_from_lse(np.array([-np.inf]), np.array([1.0])) == 0)
+
+
+def test_visited_tiles_matches_bruteforce():
+    rng = np.random.default_rng(4)
+    n, n_hat = 700, 300
+    for trial in range(4):
+        s_sel = np.sort(rng.choice(n, size=int(rng.integers(0, 40)), replace=False))
+        v_sel = np.sort(rng.choice(n, size=int(rng.integers(0, 200)), replace=False))
+        pos0 = (n - n_hat) // 128 * 128
+        want = 0
+        sset = set(int(x) for x in s_sel)
+        for bp in range(pos0, n, 128):
+            posmax = min(bp + 127, n - 1)
+            for kb in range(posmax // 64 + 1):
+                rows = range(bp, bp + 128)
+                keys = range(kb * 64, kb * 64 + 64)
+                if any((r - c) in sset for r in (bp, bp + 127) for c in keys) or any((r - c) in sset for r in rows for c in (kb * 64, kb * 64 + 63)):
+                    want += 1                                # a diagonal that crosses the tile crosses its border
+            want += -(-int((v_sel <= posmax).sum()) // 64)
+        assert metrics.visited_tiles(n, n_hat, v_sel, s_sel) == want
+    every = np.arange(n)
+    dense = metrics.visited_tiles(n, n_hat, np.arange(5), every)
+    assert dense == sum(min(bp + 127, n - 1) // 64 + 1 for bp in range((n - n_hat) // 128 * 128, n, 128))
