@@ -83,9 +83,22 @@ __global__ __launch_bounds__(1024) void plan_kernel(PlanArgs a) {
     int nvl = a.v_cnt[bh]; if (nvl > a.cap_v) nvl = a.cap_v; if (nvl < 0) nvl = 0;
     const int32_t* vl = a.v_idx + (int64_t)bh * a.cap_v;
     bool v_bad = false, s_bad = false;
-    for (int i = tid; i < nvl; i += blockDim.x) {
-        const int32_t c = vl[i];
-        v_bad = v_bad || c < 0 || c >= n || (i > 0 && vl[i - 1] >= c);
+    if ((reinterpret_cast<uintptr_t>(vl) & 15) == 0 && a.cap_v % 4 == 0) {     // four entries per load (and the one before them)
+        typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+        for (int i0 = 4 * tid; i0 < nvl; i0 += 4 * (int)blockDim.x) {
+            const i32x4 c4 = *reinterpret_cast<const i32x4*>(vl + i0);     // entries past nvl (inside the capacity, a multiple of 4 here) are not looked at
+            int32_t prev = i0 > 0 ? vl[i0 - 1] : -1;
+            const int32_t c[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (i0 + e < nvl) { v_bad = v_bad || c[e] <= prev || c[e] >= n; prev = c[e]; }
+            }
+        }
+    } else {
+        for (int i = tid; i < nvl; i += blockDim.x) {
+            const int32_t c = vl[i];
+            v_bad = v_bad || c < 0 || c >= n || (i > 0 && vl[i - 1] >= c);
+        }
     }
     v_bad = __syncthreads_or(v_bad);
     // every diagonal selected (a head the walk gave up sparsifying): the list is 0 .. n-1, checked while it is read
