@@ -26,6 +26,16 @@ int ls_debug_copy_compress_score(ls_ctx* ctx, const ls_shape* shape, float* dst_
  */
 int ls_debug_set_walk_spin_limit(ls_ctx* ctx, int32_t limit);
 
+/*
+ * Copies to the host the work queues that the most recent ls_sparse_prefill call on this context built
+ * (one queue per XCD; an item is one block of 128 query rows of one head): host_queue holds 8 arrays of
+ * B * Hq * nqb words, (batch * Hq + head) << 16 | row block, of which the first host_qlen[x] are valid;
+ * *nqb_out receives the number of row blocks per head.  `shape` must be that call's shape.  Waits for the
+ * stream.  The tests use it to check that every item is queued exactly once.
+ */
+int ls_debug_copy_prefill_queues(ls_ctx* ctx, const ls_shape* shape, uint32_t* host_queue, int32_t* host_qlen,
+                                 int32_t* nqb_out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -82,6 +82,8 @@ def load_library():
     lib.ls_poll_status.argtypes = [vp, C.POINTER(i32), vp]
     lib.ls_debug_set_walk_spin_limit.restype = C.c_int
     lib.ls_debug_set_walk_spin_limit.argtypes = [vp, i32]
+    lib.ls_debug_copy_prefill_queues.restype = C.c_int
+    lib.ls_debug_copy_prefill_queues.argtypes = [vp, sp, vp, vp, C.POINTER(i32), vp]
     lib.ls_profile_enable.restype = C.c_int
     lib.ls_profile_enable.argtypes = [vp, C.c_int]
     lib.ls_profile_prefill_kernel_ms.restype = C.c_int
@@ -193,6 +195,19 @@ class Context:
 
     def debug_set_walk_spin_limit(self, limit: int):
         self._check(self.lib.ls_debug_set_walk_spin_limit(self.h, limit))
+
+    def debug_prefill_queues(self, shape):
+        """Work queues of the last ls_sparse_prefill call: list of eight int arrays of item words."""
+        import numpy as np
+        items = shape.B * shape.Hq * ((int(shape.n) + 127) // 128 + 1)        # at least B * Hq * nqb
+        qlen = np.zeros(8, dtype=np.int32)
+        nqb = C.c_int32()
+        # the library packs the queues at the true stride B * Hq * nqb: read flat, then cut
+        flat = np.zeros(8 * items, dtype=np.uint32)
+        self._check(self.lib.ls_debug_copy_prefill_queues(self.h, C.byref(shape), flat.ctypes.data_as(C.c_void_p),
+                                                          qlen.ctypes.data_as(C.c_void_p), C.byref(nqb), _stream()))
+        stride = shape.B * shape.Hq * nqb.value
+        return [flat[x * stride: x * stride + int(qlen[x])].copy() for x in range(8)], nqb.value
 
     def profile_enable(self, on=True):
         self._check(self.lib.ls_profile_enable(self.h, 1 if on else 0))

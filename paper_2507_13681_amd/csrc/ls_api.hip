@@ -318,6 +318,38 @@ int ls_merge_lines(ls_ctx* c, const ls_shape* s,
     return LS_OK;
 }
 
+namespace {
+// Where ls_sparse_prefill keeps its per-call state in the workspace (one place, so that the test hook that
+// reads the work queues back finds them where the call put them).
+struct PrefillCarve {
+    uint32_t* obits; uint8_t* hflag; uint32_t* cost; uint16_t* pref; uint32_t* queue; int32_t* qlen; int32_t* qhead; uint8_t* tab;
+    int nqb; int64_t pos0; int code;
+};
+const char* carve_prefill(ls_ctx* c, const ls_shape* s, PrefillCarve& w) {
+    const int BH = s->B * s->Hq;
+    const int words = words_of(s->n), tab_len = tab_len_of(s->n);
+    Bump bp{c->ws, c->ws_bytes, 0};
+    w.obits = bp.take<uint32_t>((size_t)BH * (words + 1));
+    w.hflag = bp.take<uint8_t>((size_t)BH);
+    w.cost = bp.take<uint32_t>((size_t)BH);
+    w.pref = bp.take<uint16_t>((size_t)BH * (tab_len + 1));
+    const int bm = ls::prefill_block_rows();
+    w.pos0 = (s->n - s->n_hat) / bm * bm;
+    w.nqb = (int)((s->n - w.pos0 + bm - 1) / bm);
+    w.code = LS_ESHAPE;
+    if (w.nqb > 65535) return "too many row blocks";
+    if (BH > 8192) return "B * Hq exceeds 8192";
+    w.queue = bp.take<uint32_t>(8 * (size_t)BH * w.nqb);
+    w.qlen = bp.take<int32_t>(8);
+    w.qhead = bp.take<int32_t>(8);
+    w.tab = bp.take<uint8_t>((size_t)BH * tab_len);
+    w.code = LS_EWORKSPACE;
+    if (!bp.ok()) return "workspace is too small";
+    w.code = LS_OK;
+    return nullptr;
+}
+}  // namespace
+
 int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k, const void* v,
                       const int32_t* v_idx, const int32_t* v_cnt, int32_t cap_v,
                       const int32_t* s_idx, const int32_t* s_cnt, int32_t cap_s,
@@ -333,21 +365,11 @@ int ls_sparse_prefill(ls_ctx* c, const ls_shape* s, const void* q, const void* k
     const int words = words_of(s->n), tab_len = tab_len_of(s->n);
     if (ls::prefill_smem_bytes(s->dtype, s->d, words, tab_len) > 160 * 1024)
         return fail(c, LS_ESHAPE, "ls_sparse_prefill: n too large for the LDS bitmaps");
-    Bump bp{c->ws, c->ws_bytes, 0};
-    uint32_t* obits = bp.take<uint32_t>((size_t)BH * (words + 1));
-    uint8_t* hflag = bp.take<uint8_t>((size_t)BH);
-    uint32_t* cost = bp.take<uint32_t>((size_t)BH);
-    uint16_t* pref = bp.take<uint16_t>((size_t)BH * (tab_len + 1));
-    const int bm = ls::prefill_block_rows();
-    const int64_t pos0 = (s->n - s->n_hat) / bm * bm;
-    const int nqb = (int)((s->n - pos0 + bm - 1) / bm);
-    if (nqb > 65535) return fail(c, LS_ESHAPE, "ls_sparse_prefill: too many row blocks");
-    if (BH > 8192) return fail(c, LS_ESHAPE, "ls_sparse_prefill: B * Hq exceeds 8192");
-    uint32_t* queue = bp.take<uint32_t>(8 * (size_t)BH * nqb);
-    int32_t* qlen = bp.take<int32_t>(8);
-    int32_t* qhead = bp.take<int32_t>(8);
-    uint8_t* tab = bp.take<uint8_t>((size_t)BH * tab_len);
-    if (!bp.ok()) return fail(c, LS_EWORKSPACE, "ls_sparse_prefill: workspace of %zu bytes is too small", c->ws_bytes);
+    PrefillCarve w;
+    if (const char* m = carve_prefill(c, s, w)) return fail(c, w.code, "ls_sparse_prefill: %s", m);
+    uint32_t* obits = w.obits; uint8_t* hflag = w.hflag; uint32_t* cost = w.cost; uint16_t* pref = w.pref;
+    uint32_t* queue = w.queue; int32_t* qlen = w.qlen; int32_t* qhead = w.qhead; uint8_t* tab = w.tab;
+    const int nqb = w.nqb; const int64_t pos0 = w.pos0;
     if (hipSetDevice(c->device) != hipSuccess) return fail(c, LS_EHIP, "ls_sparse_prefill: hipSetDevice failed");
     ls::PlanArgs p{};
     p.n = s->n; p.words = words; p.tab_len = tab_len; p.v_idx = v_idx; p.v_cnt = v_cnt; p.s_idx = s_idx; p.s_cnt = s_cnt;
@@ -548,6 +570,23 @@ int ls_poll_status(ls_ctx* c, int32_t* host_out, void* stream) {
 int ls_debug_set_walk_spin_limit(ls_ctx* c, int32_t limit) {
     if (!c) return LS_EINVAL;
     c->walk_spin_limit = limit < 0 ? ls::WALK_SPIN_DEFAULT : limit;
+    return LS_OK;
+}
+
+/* Debug / test hook: the eight work queues the last ls_sparse_prefill call on this context built
+ * (host_queue: [8][B*Hq*nqb] item words = (head << 16) | row block, host_qlen: [8]); synchronises the stream. */
+int ls_debug_copy_prefill_queues(ls_ctx* c, const ls_shape* s, uint32_t* host_queue, int32_t* host_qlen, int32_t* nqb_out, void* stream) {
+    if (!c || !s || !host_queue || !host_qlen || !nqb_out) return LS_EINVAL;
+    if (check_shape(s, true, false, true)) return LS_ESHAPE;
+    PrefillCarve w;
+    if (carve_prefill(c, s, w)) return w.code;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t items = (size_t)s->B * s->Hq * w.nqb;
+    if (hipSetDevice(c->device) != hipSuccess) return LS_EHIP;
+    if (hipMemcpyAsync(host_queue, w.queue, 8 * items * sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess) return LS_EHIP;
+    if (hipMemcpyAsync(host_qlen, w.qlen, 8 * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess) return LS_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return LS_EHIP;
+    *nqb_out = w.nqb;
     return LS_OK;
 }
 

@@ -152,6 +152,15 @@ def block_rows(cfg, sel, rng, heads_per_kind=2, random_blocks=8):
     return np.array(sorted(set(rows)), np.int64)
 
 
+def check_queues(pipe):
+    """The work queues of the attention kernel hold every (head, 128-row block) item exactly once."""
+    queues, nqb = pipe.ctx.debug_prefill_queues(pipe.shape)
+    items = np.concatenate(queues).astype(np.int64)
+    BH = pipe.shape.B * pipe.shape.Hq
+    expect = (np.arange(BH, dtype=np.int64)[:, None] << 16 | np.arange(nqb, dtype=np.int64)[None, :]).ravel()
+    np.testing.assert_array_equal(np.sort(items), np.sort(expect))
+
+
 def run_prefill_config(oracle, name, alphas=None, per_head=6, all_rows=False, dense_mode=False):
     cfg = inputs.CONFIGS[name]
     print(f"[{name}] generating inputs", flush=True)
@@ -177,6 +186,7 @@ def run_prefill_config(oracle, name, alphas=None, per_head=6, all_rows=False, de
         print(f"[{name}] alpha={alpha}: density {dens:.4f}, lines tolerated at the threshold: {tol_order} by weight, "
               f"{tol_stop} by the stop rule", flush=True)
         out, lse = pipe.prefill(sel_dev, sentinel=True)
+        check_queues(pipe)
         torch.cuda.synchronize()
         assert pipe.ctx.ls_poll_status() == 0
         # every row written by some work item: no sentinel left (an empty row is zeros / -inf, never NaN)
@@ -276,6 +286,7 @@ def test_maximum_context_length(oracle):
         tolerated = check_selection(sel_gpu, sel_ref, sc_ref, alpha)
         print(f"[max_n] alpha={alpha}: counts v {sel_gpu['v_cnt'].ravel().tolist()} s {sel_gpu['s_cnt'].ravel().tolist()}, tolerated {tolerated}", flush=True)
         out, lse = pipe.prefill(sel_dev, sentinel=True)
+        check_queues(pipe)
         torch.cuda.synchronize()
         assert not bool(torch.isnan(out).any()) and not bool(torch.isnan(lse).any())
         rng = np.random.default_rng(1)
@@ -298,6 +309,7 @@ def test_first_turn_prefill(oracle):
     check_selection(sel_gpu, sel_ref, sc_ref, 0.9)
     print("[first_turn] prefill of all rows", flush=True)
     out, lse = pipe.prefill(sel_dev, sentinel=True)
+    check_queues(pipe)
     torch.cuda.synchronize()
     assert not bool(torch.isnan(out).any()) and not bool(torch.isnan(lse).any())
     rows = np.arange(cfg.B * cfg.Hq * cfg.n_hat, dtype=np.int64)
