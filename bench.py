@@ -201,7 +201,7 @@ def main():
     cells = metrics.selection_cells(cfg.n, cfg.n_hat, sel_h)
 
     # What each kind of head costs the attention kernel.  The kernel's time per visited tile hardly depends on the tile
-    # (the design doc, section 6), so the measured kernel time is split between the kinds in proportion to the 128 x 64 tiles
+    # (its four waves move from barrier to barrier together), so the measured kernel time is split between the kinds in proportion to the 128 x 64 tiles
     # their heads make the kernel visit (counted on the host from the index sets, as the kernel's own plan does).
     nvh, nsh = sel_h["v_cnt"], sel_h["s_cnt"]
     kind_masks = {"exhausted": (nvh >= cfg.n) & (nsh >= cfg.n), "slash_only": (nvh == 0) & (nsh > 0),
