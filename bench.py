@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--exact-overlap", action="store_true",
                     help="select with ls_score_window + ls_select_exact (overlaps counted cell by cell) instead of ls_select; "
                          "not the headline configuration")
+    ap.add_argument("--first-turn", action="store_true",
+                    help="every position of the context is a new row (n_hat = n): the first turn of a dialogue; not the "
+                         "headline configuration")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel, measured by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
                          "this same command (see profiles/); counters cannot be read inside a timed run, so roofline.traffic is "
@@ -113,6 +116,8 @@ def main():
         return
 
     cfg = inputs.CONFIGS[args.workload]
+    if args.first_turn:
+        cfg = inputs.scaled(cfg, n_hat=cfg.n)
     alpha = cfg.alpha if args.alpha is None else args.alpha
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     q, k, v, _ = inputs.make_inputs(cfg)
