@@ -771,21 +771,40 @@ __global__ void rank_kernel(SelectArgs a) {
     if (i < a.n) a.sidx0[seg + a.sidx1[seg + i]] = (int32_t)i;
 }
 
-constexpr int XW_THREADS = 192;                // wave 0 walks, waves 1 / 2 stage the records of the slash / column list
-constexpr int XW_CELLS = 2048;                 // cells of staged records per list: a ring of XW_CELLS / wpad records
+constexpr int XW_STAGERS = 3;                  // staging waves per list
+constexpr int XW_THREADS = 64 * (1 + 2 * XW_STAGERS);   // wave 0 walks, then XW_STAGERS waves per list stage its records
+constexpr int XW_CELLS = 4096;                 // cells of staged records per list: a ring of XW_CELLS / wpad records
 constexpr int XW_BATCH = 8;                    // records a stager fetches per round trip
 struct XwSync { int staged[2], head[2], done, err; };
 
+// Sum of a double over the 64 lanes, the same value in every lane.  Data-parallel-primitive moves on the two
+// halves of the value instead of cross-lane reads through LDS: a shuffle of a double is two LDS round trips, six
+// steps of them were most of the time of a pick.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double x) {      // lanes outside ROW_MASK receive 0
+    const uint64_t u = __builtin_bit_cast(uint64_t, x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, ROW_MASK, 0xF, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ double wave_sum_f64(double x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-    return x;
+    x += dpp_f64<0xB1, 0xF>(x);                            // quad_perm [1,0,3,2]
+    x += dpp_f64<0x4E, 0xF>(x);                            // quad_perm [2,3,0,1]: every lane holds its quad's sum
+    x += dpp_f64<0x141, 0xF>(x);                           // row_half_mirror: sums of 8
+    x += dpp_f64<0x140, 0xF>(x);                           // row_mirror: every lane holds its row's (16 lanes) sum
+    x += dpp_f64<0x142, 0xA>(x);                           // row_bcast15 into rows 1 and 3
+    x += dpp_f64<0x143, 0xC>(x);                           // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    const uint64_t u = __builtin_bit_cast(uint64_t, x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, 63), hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), 63);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 
 // grid (BH).  LDS: per list a ring of records (wpad cells + wpad ranks each) and per-record line index / weight.
+// NC: cells of a record per lane held in registers (1, 2 or 4; a window of w rows needs ceil(w / 64))
+template <int NC>
 __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
     extern __shared__ __align__(16) unsigned char xw_lds[];
-    const int W = a.w, wpad = (W + 63) / 64 * 64, CP = wpad / 64, ring = XW_CELLS / wpad;      // ring >= 8 (w <= 256)
+    const int W = a.w, wpad = (W + 63) / 64 * 64, CP = wpad / 64, ring = XW_CELLS / wpad;      // ring >= 16 (w <= 256)
     float* cells = reinterpret_cast<float*>(xw_lds);                       // [2][ring][wpad]
     int32_t* ranks = reinterpret_cast<int32_t*>(cells + 2 * XW_CELLS);     // [2][ring][wpad]
     int32_t* ridx = ranks + 2 * XW_CELLS;                                  // [2][ring] line index of a record
@@ -800,41 +819,35 @@ __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
 
     if (wv != 0) {
         // ------------------------------------------------------------------ staging of one list
-        const int l = wv - 1;                                              // 0: slashes, 1: columns
+        // XW_STAGERS waves per list take the batches of XW_BATCH records in turn (stager s: batches s, s + S, ...),
+        // so that the memory round trips of consecutive batches overlap; a batch is published in order, once the
+        // batch before it has been.
+        const int l = (wv - 1) / XW_STAGERS, sidx = (wv - 1) % XW_STAGERS; // list (0: slashes, 1: columns), stager
         const int32_t* sorted = a.sidx1 + ((int64_t)l * a.BH + bh) * a.n;
         const int32_t* rank_other = a.sidx0 + ((int64_t)(1 - l) * a.BH + bh) * a.n;
         const float* wts = (l == 0 ? a.slash : a.vert) + (int64_t)bh * a.n;
         const float* A = a.a_win + (int64_t)bh * W * a.n;
-        int pos[4];                                                        // positions of this lane's rows t = lane + 64 c
+        int pos[NC];                                                        // positions of this lane's rows t = lane + 64 c
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < NC; ++c) {
             const int t = lane + 64 * c;
             int64_t p = t < W ? (a.q_pos ? a.q_pos[t] : (int64_t)n - W + t) : -1;
             if (p > n - 1) p = n - 1;
             pos[c] = (int)p;
         }
-        int j = 0, spins = 0;
-        while (j < n && walk_ld(&sync->done) == 0) {
-            const int room = walk_ld(&sync->head[l]) + ring - j;           // records that may be written
-            if (room <= 0) {
-                __builtin_amdgcn_s_sleep(2);
-                if (++spins > spin_limit) { walk_st(&sync->err, 1); break; }
-                continue;
-            }
-            spins = 0;
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            int batch = room < XW_BATCH ? room : XW_BATCH;
-            if (batch > n - j) batch = n - j;
+        for (int j = sidx * XW_BATCH; j < n; j += XW_STAGERS * XW_BATCH) {
+            const int batch = n - j < XW_BATCH ? n - j : XW_BATCH;
+            // the loads do not depend on the ring: issued before waiting for room
             int32_t idx[XW_BATCH];
 #pragma unroll
             for (int r = 0; r < XW_BATCH; ++r) idx[r] = sorted[j + (r < batch ? r : 0)];
-            float wt[XW_BATCH], cell[XW_BATCH][4];
-            int32_t rk[XW_BATCH][4];
+            float wt[XW_BATCH], cell[XW_BATCH][NC];
+            int32_t rk[XW_BATCH][NC];
 #pragma unroll
             for (int r = 0; r < XW_BATCH; ++r) {
                 wt[r] = wts[idx[r]];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
+                for (int c = 0; c < NC; ++c) {
                     cell[r][c] = 0.f; rk[r][c] = 0x7FFFFFFF;
                     if (c < CP) {
                         const int t = lane + 64 * c;
@@ -847,12 +860,21 @@ __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
                     }
                 }
             }
+            // room for the whole batch: its last record may be written once record j + batch - 1 - ring has been left
+            bool stop = false;
+            for (int spins = 0; walk_ld(&sync->head[l]) + ring < j + batch; ) {
+                if (walk_ld(&sync->done) != 0) { stop = true; break; }
+                __builtin_amdgcn_s_sleep(2);
+                if (++spins > spin_limit) { walk_st(&sync->err, 1); stop = true; break; }
+            }
+            if (stop) break;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 #pragma unroll
             for (int r = 0; r < XW_BATCH; ++r) {
                 if (r < batch) {
                     const int slot = (j + r) % ring;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
+                    for (int c = 0; c < NC; ++c)
                         if (c < CP) {
                             cells[(l * ring + slot) * wpad + lane + 64 * c] = cell[r][c];
                             ranks[(l * ring + slot) * wpad + lane + 64 * c] = rk[r][c];
@@ -860,10 +882,16 @@ __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
                     if (lane == 0) { ridx[l * 256 + slot] = idx[r]; rwt[l * 256 + slot] = wt[r]; }
                 }
             }
+            // in-order publication: wait until every earlier batch is out
+            for (int spins = 0; walk_ld(&sync->staged[l]) != j; ) {
+                if (walk_ld(&sync->done) != 0) { stop = true; break; }
+                __builtin_amdgcn_s_sleep(1);
+                if (++spins > spin_limit) { walk_st(&sync->err, 1); stop = true; break; }
+            }
+            if (stop) break;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
-            j += batch;
-            if (lane == 0) walk_st(&sync->staged[l], j);
+            if (lane == 0) walk_st(&sync->staged[l], j + batch);
         }
         return;
     }
@@ -875,20 +903,23 @@ __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
     int is = 0, iv = 0;
     bool failed = false;
     // head record of each list, read again only when that head moves
-    float c_s[4], c_v[4], w_s = 0.f, w_v = 0.f, l_s = 1.f, l_v = 1.f;
-    int32_t r_s[4], r_v[4];
+    float c_s[NC], c_v[NC], w_s = 0.f, w_v = 0.f, l_s = 1.f, l_v = 1.f;
+    int32_t r_s[NC], r_v[NC];
+    int seen[2] = {0, 0};                                  // records of each list known to be staged (the counter is re-read only past that)
     auto wait_record = [&](int l, int want) {              // until record `want` of list l is staged
-        int spins = 0;
-        while (walk_ld(&sync->staged[l]) <= want) {
+        if (want < seen[l]) return;
+        int spins = 0, st;
+        while ((st = walk_ld(&sync->staged[l])) <= want) {
             __builtin_amdgcn_s_sleep(1);
             if (++spins > spin_limit || walk_ld(&sync->err)) { failed = true; break; }
         }
+        seen[l] = st;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     };
-    auto read_record = [&](int l, int h, float (&c)[4], int32_t (&r)[4], float& wt, float& len) {
+    auto read_record = [&](int l, int h, float (&c)[NC], int32_t (&r)[NC], float& wt, float& len) {
         const int slot = h % ring;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NC; ++q) {
             c[q] = 0.f; r[q] = 0x7FFFFFFF;
             if (q < CP) { c[q] = cells[(l * ring + slot) * wpad + lane + 64 * q]; r[q] = ranks[(l * ring + slot) * wpad + lane + 64 * q]; }
         }
@@ -897,18 +928,34 @@ __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
         const float rest = (float)(n - line);
         len = rest < nh ? rest : nh;
     };
-    auto overlap = [&](const float (&c)[4], const int32_t (&r)[4], int taken_other) -> float {
+    auto overlap = [&](const float (&c)[NC], const int32_t (&r)[NC], int taken_other) -> float {
         double x = 0.0;
+        bool any = false;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) x += r[q] < taken_other ? (double)c[q] : 0.0;
+        for (int q = 0; q < NC; ++q) { const bool in = r[q] < taken_other; any |= in; x += in ? (double)c[q] : 0.0; }
+        if (__ballot(any) == 0ull) return 0.f;             // no crossed line taken yet: nothing to add up
         return (float)wave_sum_f64(x);
     };
+    // the heads are published (slots handed back to the stagers) every eighth pick
     if (n > 0) { wait_record(0, 0); wait_record(1, 0); }
     if (!failed) { read_record(0, 0, c_s, r_s, w_s, l_s); read_record(1, 0, c_v, r_v, w_v, l_v); }
+    float ol_s = 0.f, ol_v = 0.f;
+    bool dirty_s = true, dirty_v = true;
+    auto crosses = [&](const int32_t (&r)[NC], int rank) -> bool {       // does the line of that rank cross this head's cells?
+        bool hit = false;
+#pragma unroll
+        for (int q = 0; q < NC; ++q) hit |= r[q] == rank;
+        return __ballot(hit) != 0ull;
+    };
+    int picks = 0;
     while (!failed && sum < target && (is < n || iv < n)) {
         const bool has_s = is < n, has_v = iv < n;
-        const float ds = has_s ? __fsub_rn(w_s, overlap(c_s, r_s, iv)) : 0.f;
-        const float dv = has_v ? __fsub_rn(w_v, overlap(c_v, r_v, is)) : 0.f;
+        // an overlap is summed again only when its set of taken crossed lines changed: a new list head, or the
+        // line just taken from the other list crosses this head inside the window
+        if (has_s && dirty_s) { ol_s = overlap(c_s, r_s, iv); dirty_s = false; }
+        if (has_v && dirty_v) { ol_v = overlap(c_v, r_v, is); dirty_v = false; }
+        const float ds = has_s ? __fsub_rn(w_s, ol_s) : 0.f;
+        const float dv = has_v ? __fsub_rn(w_v, ol_v) : 0.f;
         bool take_s;
         if (!has_v) take_s = true;
         else if (!has_s) take_s = false;
@@ -920,15 +967,19 @@ __global__ __launch_bounds__(XW_THREADS) void walk_exact_kernel(SelectArgs a) {
         if (take_s) {
             sum = __fadd_rn(sum, ds);
             ++is;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the record left behind
-            if (lane == 0) walk_st(&sync->head[0], is);
+            dirty_s = true;
+            dirty_v = dirty_v || crosses(r_v, is - 1);
             if (is < n && !(sum >= target)) { wait_record(0, is); if (!failed) read_record(0, is, c_s, r_s, w_s, l_s); }
         } else {
             sum = __fadd_rn(sum, dv);
             ++iv;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            if (lane == 0) walk_st(&sync->head[1], iv);
+            dirty_v = true;
+            dirty_s = dirty_s || crosses(r_s, iv - 1);
             if (iv < n && !(sum >= target)) { wait_record(1, iv); if (!failed) read_record(1, iv, c_v, r_v, w_v, l_v); }
+        }
+        if ((++picks & 7) == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // done reading the records left behind
+            if (lane == 0) { walk_st(&sync->head[0], is); walk_st(&sync->head[1], iv); }
         }
     }
     if (lane == 0) {
@@ -1278,7 +1329,9 @@ hipError_t init_select_kernels() {
     if ((e = allow_full_lds(&sort_merge_kernel<4096>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&sort_merge_kernel<SORT_SEG_MAX>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&walk_kernel)) != hipSuccess) return e;
-    if ((e = allow_full_lds(&walk_exact_kernel)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&walk_exact_kernel<1>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&walk_exact_kernel<2>)) != hipSuccess) return e;
+    if ((e = allow_full_lds(&walk_exact_kernel<4>)) != hipSuccess) return e;
     if ((e = allow_full_lds(&merge_lines_kernel)) != hipSuccess) return e;
     return allow_full_lds(&emit_kernel);
 }
@@ -1305,7 +1358,9 @@ hipError_t run_select_exact(const SelectArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((a.n + 255) / 256), a.BH, 2), dim3(256), 0, st, a);
     const size_t xw = 2 * XW_CELLS * 8 + 2 * 256 * 8 + sizeof(XwSync) + 16;
-    hipLaunchKernelGGL(walk_exact_kernel, dim3(a.BH), dim3(XW_THREADS), xw, st, a);
+    if (a.w <= 64) hipLaunchKernelGGL(walk_exact_kernel<1>, dim3(a.BH), dim3(XW_THREADS), xw, st, a);
+    else if (a.w <= 128) hipLaunchKernelGGL(walk_exact_kernel<2>, dim3(a.BH), dim3(XW_THREADS), xw, st, a);
+    else hipLaunchKernelGGL(walk_exact_kernel<4>, dim3(a.BH), dim3(XW_THREADS), xw, st, a);
     const size_t smem = (size_t)((a.n + 31) / 32) * 4;
     hipLaunchKernelGGL(emit_kernel, dim3(2, a.BH), dim3(1024), smem, st, a);
     return hipGetLastError();
